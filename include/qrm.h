@@ -1,0 +1,192 @@
+/*
+ * qrm.h - C ABI of the MI355X (gfx950) batched watermark-detection library.
+ *
+ * The library computes, for a batch of images, what the detection stage of the
+ * paper computes per image (Section 4.3 "Detection with Reed-Solomon
+ * Correction"): one l x l tile is cropped from the image and normalised
+ * (Table 1: toTensor, normalize; tile strategies random / random grid / fixed),
+ * the convolutional extractor H_D turns the tile into N soft bits (Section
+ * 4.1), the soft bits are thresholded at zero, grouped into m-bit symbols and
+ * Reed-Solomon decoded over GF(2^m) (Appendix B).  Per image the caller gets
+ * the triple the paper's decoder returns (Appendix B, after "Berlekamp-Welch
+ * Decoding"): corrected message, corrected codeword, number of corrected
+ * symbols.
+ *
+ * Conventions common to every call
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; everything
+ *     else is HOST memory.  The library never frees or keeps caller memory,
+ *     except that a context copies (and converts) the weights at creation.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without waiting.
+ *   - Return value is a qrm_status; nothing aborts or throws.  On anything but
+ *     QRM_OK no kernel of that call has been launched unless stated, and
+ *     qrm_last_error() describes the reason.
+ *   - N == 0 is a successful no-op.
+ *   - A context belongs to one device and one host thread at a time.  Work on
+ *     up to QRM_MAX_STREAMS different streams may be in flight: each stream
+ *     gets its own workspace inside the context.
+ */
+#ifndef QRM_H
+#define QRM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QRM_MAX_STREAMS 8
+
+#if defined(__GNUC__)
+#define QRM_API __attribute__((visibility("default")))
+#else
+#define QRM_API
+#endif
+
+typedef struct qrm_ctx qrm_ctx; /* opaque, library-owned */
+
+typedef enum {
+    QRM_OK = 0,
+    QRM_E_INVALID = 1,     /* bad argument (NULL pointer, shape, code parameters) */
+    QRM_E_UNSUPPORTED = 2, /* valid but outside what the kernels are built for */
+    QRM_E_NOMEM = 3,       /* workspace allocation failed */
+    QRM_E_DEVICE = 4       /* a HIP call failed */
+} qrm_status;
+
+/*
+ * The extractor H_D (Section 4.1: a HiDDeN-style convolutional extractor that maps a
+ * tile to N soft bits).  Architecture, as fixed by the benchmark configurations:
+ *   block b = 0..n_blocks-1 : conv3x3 (stride 1, zero pad 1, no flip) -> *scale + bias -> ReLU
+ *                             block 0 maps in_ch -> channels, the others channels -> channels
+ *   final conv3x3 channels -> n_bits (optional affine, optional ReLU), global average pool,
+ *   linear n_bits x n_bits (+ bias), logits.
+ * The input is normalised as x = (u8/255 - mean[c]) / std[c]; padding is zero in the
+ * normalised domain and never looks outside the tile.
+ * All pointers are HOST fp32 arrays, read during qrm_create only.
+ */
+typedef struct {
+    int32_t in_ch;       /* 3 */
+    int32_t n_blocks;    /* >= 1 */
+    int32_t channels;    /* 32 or 64 */
+    int32_t n_bits;      /* 1..128 */
+    const float *conv_w; /* OIHW, concatenated: [C,in_ch,3,3], (n_blocks-1) x [C,C,3,3], [n_bits,C,3,3] */
+    const float *scale;  /* [n_blocks*C] (+ n_bits more if final_affine); NULL = all ones */
+    const float *bias;   /* same length as scale; NULL = all zeros */
+    int32_t final_affine; /* 1: scale/bias carry n_bits extra entries applied to the final conv */
+    int32_t final_relu;  /* 1: ReLU after the final conv (0 in every benchmark configuration) */
+    const float *lin_w;  /* [n_bits,n_bits] row-major (out,in) */
+    const float *lin_b;  /* [n_bits] or NULL */
+    float mean[3], std[3];
+} qrm_extractor_desc;
+
+/*
+ * The Reed-Solomon code (Appendix B "Notation"): m-bit symbols, length n <= 2^m - 1, k message
+ * symbols, t = (n-k)/2 correctable symbol errors.  Narrow-sense BCH view: the generator
+ * polynomial has roots alpha^fcr .. alpha^(fcr+2t-1), alpha = x.  n < 2^m - 1 is the shortened
+ * code (the highest powers are dropped).  Symbol 0 of a word is the highest-degree coefficient;
+ * the message occupies the first k symbols.
+ */
+typedef struct {
+    int32_t m;          /* 2..8 */
+    uint32_t prim_poly; /* e.g. 0x13 for m=4, 0x11D for m=8; must be primitive */
+    int32_t n, k;       /* 0 < k < n <= 2^m - 1, n - k even, (n-k)/2 <= 8 */
+    int32_t fcr;        /* first consecutive root, >= 0 (1 in the benchmark configurations) */
+} qrm_rs_desc;
+
+/*
+ * Create a context on `device`.  Either descriptor may be NULL; calls that need the missing half
+ * then return QRM_E_INVALID.  Weights are converted to bf16 MFMA operand layout (folded scale) and
+ * uploaded; GF(2^m) log/antilog tables are built and uploaded.
+ * Errors: QRM_E_INVALID for NULL out pointer / inconsistent descriptor (n > 2^m-1, odd n-k, non-
+ * primitive polynomial, channels not 32/64, ...), QRM_E_UNSUPPORTED for t > 8, QRM_E_DEVICE.
+ * On failure *out is NULL and qrm_last_error(NULL) holds the message.
+ */
+QRM_API qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int device, qrm_ctx **out);
+
+/* Waits for the context's streams, frees its device memory.  NULL is ignored. */
+QRM_API void qrm_destroy(qrm_ctx *ctx);
+
+/* Message of the last failing call on `ctx` (or of the last failing qrm_create if ctx == NULL).
+ * The string is owned by the library and valid until the next failing call. */
+QRM_API const char *qrm_last_error(const qrm_ctx *ctx);
+
+/*
+ * Images per internal micro-batch of the extractor (activations of one micro-batch ping-pong
+ * between two workspace buffers so that they stay cache-resident).  0 restores the default.
+ */
+QRM_API qrm_status qrm_set_micro_batch(qrm_ctx *ctx, int32_t images);
+
+/* Bytes of device workspace one stream of this context needs for a call with these sizes. */
+QRM_API size_t qrm_workspace_bytes(const qrm_ctx *ctx, int64_t N, int32_t tile_h, int32_t tile_w);
+
+/*
+ * Tile crop (Section 4.3; Table 1 "Tile"): d_tiles[i][c][y][x] = d_images[i][c][oy+y][ox+x] with
+ * (oy,ox) = d_off_yx[i] clamped to [0,H-tile] x [0,W-tile] (all three tiling strategies reduce to
+ * an origin).  d_images u8 [N,3,H,W] planar; d_off_yx i32 [N,2] or NULL (= origin 0,0);
+ * d_tiles u8 [N,3,tile,tile].  Bit-exact copy.
+ * Errors: QRM_E_INVALID if tile <= 0, tile > H, tile > W, or a required pointer is NULL.
+ */
+QRM_API qrm_status qrm_extract_tiles(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                             const int32_t *d_off_yx, int32_t tile, uint8_t *d_tiles, void *stream);
+
+/*
+ * Extractor forward pass on raw tiles (Section 4.1, m' = H_D(tile); hard bit = (logit > 0)).
+ * d_tiles u8 [N,3,h,w] raw bytes, normalised inside the first convolution.
+ * d_logits f32 [N,n_bits]; d_bits u8 [N,n_bits] with values 0/1, may be NULL.
+ * Errors: QRM_E_INVALID (no extractor in ctx, NULL pointer, h or w < 1), QRM_E_NOMEM.
+ */
+QRM_API qrm_status qrm_extractor_forward(qrm_ctx *ctx, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w,
+                                 float *d_logits, uint8_t *d_bits, void *stream);
+
+/*
+ * Diagnostic companion of qrm_extractor_forward: runs blocks 0..n_run-1 only (1 <= n_run <=
+ * n_blocks) and writes that block's output activations, converted from the internal bf16 NHWC
+ * layout, to d_act f32 [N,channels,h,w].  Same kernels as the full pass.
+ */
+QRM_API qrm_status qrm_extractor_blocks(qrm_ctx *ctx, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w,
+                                int32_t n_run, float *d_act, void *stream);
+
+/*
+ * Batched bounded-distance Reed-Solomon decoding (Appendix B; same function as the paper's
+ * Berlekamp-Welch decoder, computed by syndromes, Berlekamp-Massey, Chien search and Forney).
+ * d_symbols u8 [N,n], one symbol per byte (bits above m are ignored).
+ * d_msg u8 [N,k]; d_codeword u8 [N,n] or NULL; d_nerr i8 [N]: number of corrected symbols 0..t,
+ * or -1 when no codeword lies within distance t - then d_msg / d_codeword carry the received
+ * symbols unchanged.  An uncorrectable word is not an error status.
+ * Errors: QRM_E_INVALID (no code in ctx, NULL pointer, N < 0).
+ */
+QRM_API qrm_status qrm_rs_decode(qrm_ctx *ctx, const uint8_t *d_symbols, int64_t N,
+                         uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
+
+/*
+ * The whole detection path on a batch resident in device memory: crop + normalise fused into the
+ * first convolution, extractor, threshold, MSB-first bit->symbol packing (symbol j = bits
+ * j*m .. j*m+m-1), RS decode.  Requires n_bits == n*m.
+ * d_images u8 [N,3,H,W]; d_off_yx i32 [N,2] or NULL; tile = l.
+ * d_logits f32 [N,n_bits] or NULL; d_bits u8 [N,n_bits] or NULL;
+ * d_msg u8 [N,k]; d_codeword u8 [N,n] or NULL; d_nerr i8 [N].
+ * Errors: as above, plus QRM_E_INVALID when n_bits != n*m.
+ */
+QRM_API qrm_status qrm_detect(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                      const int32_t *d_off_yx, int32_t tile,
+                      float *d_logits, uint8_t *d_bits,
+                      uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
+
+/*
+ * Per-launch timing of the dominant kernel (the C -> C convolution), for benchmarks: while enabled,
+ * every launch of that kernel is bracketed by two hipEvents recorded on the stream it is launched on.
+ * qrm_profile_read waits for the recorded events, returns the summed duration in milliseconds, the
+ * number of launches and their algorithmic FLOPs (2*9*C*C*h*w per image), and clears the record.
+ * Any output pointer may be NULL.
+ */
+QRM_API qrm_status qrm_profile_enable(qrm_ctx *ctx, int32_t on);
+QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, double *ms_total, int64_t *launches, double *flops);
+
+/* Library version string, e.g. "qrm 0.1 gfx950". */
+QRM_API const char *qrm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QRM_H */

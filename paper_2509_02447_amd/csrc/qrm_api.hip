@@ -1,0 +1,534 @@
+// C ABI of libqrm: context, weight / table preparation, workspace, and the entry points that chain the
+// kernels of the detection path (Section 4.3 of the paper; kernels in extractor.hip, rs_decode.hip,
+// tiles.hip).  Host code only; no arithmetic of the method runs on the CPU after qrm_create.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "qrm_internal.h"
+
+using namespace qrm;
+
+namespace qrm {
+
+uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u)); // inf / nan
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+} // namespace qrm
+
+namespace {
+
+struct Slot {
+    bool used = false;
+    hipStream_t stream = nullptr;
+    void *ws = nullptr;
+    size_t bytes = 0;
+};
+
+std::string g_create_error;
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// MFMA row r of a 32-row weight fragment carries output channel perm32(r) of its block, so that the
+// 16 accumulators of a lane are 16 consecutive channels.
+int perm32(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
+
+} // namespace
+
+struct qrm_ctx {
+    int device = 0;
+    int num_cu = 256;
+    bool has_ext = false, has_rs = false;
+    // extractor
+    int n_blocks = 0, C = 0, n_bits = 0, nbp = 0, final_relu = 0, final_affine = 0;
+    float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
+    void *d_weights = nullptr;  // one allocation: all fragments, biases, linear layer
+    const bf16_t *d_w_first = nullptr;
+    std::vector<const bf16_t *> d_w_mid;
+    const bf16_t *d_w_final = nullptr;
+    const float *d_bias = nullptr;        // [n_blocks*C]
+    const float *d_bias_final = nullptr;  // [nbp] or null
+    const float *d_lin_w = nullptr, *d_lin_b = nullptr;
+    // code
+    RsParams rs{};
+    void *d_tables = nullptr;
+    // workspace
+    int micro_batch = 0; // 0 = default
+    Slot slots[QRM_MAX_STREAMS];
+    // optional per-launch timing of the C -> C convolution kernel (hipEvents on the launch stream)
+    bool profile = false;
+    std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
+    size_t ev_used = 0;
+    double prof_flops = 0.0;          // algorithmic FLOPs of the timed launches
+    std::string err;
+};
+
+namespace {
+
+qrm_status fail(qrm_ctx *c, qrm_status st, const std::string &msg)
+{
+    if (c) c->err = msg; else g_create_error = msg;
+    return st;
+}
+
+qrm_status hip_fail(qrm_ctx *c, hipError_t e, const char *what)
+{
+    return fail(c, QRM_E_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+// ---- weights -> MFMA A-fragment order ------------------------------------------------------------
+// fragment element (blk, tap, kc, lane, e): output channel blk*32 + perm32(lane%32),
+// input channel kc*16 + (lane/32)*8 + e.  w is OIHW [cout][cin][3][3]; rows >= cout are zero.
+void pack_mid(const float *w, const float *scale, int cout, int cout_pad, int cin, std::vector<uint16_t> &dst)
+{
+    const int KC = cin / 16;
+    for (int blk = 0; blk < cout_pad / 32; ++blk)
+        for (int tap = 0; tap < 9; ++tap)
+            for (int kc = 0; kc < KC; ++kc)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e) {
+                        const int o = blk * 32 + perm32(lane & 31);
+                        const int ci = kc * 16 + (lane >> 5) * 8 + e;
+                        float v = 0.f;
+                        if (o < cout) v = w[((size_t)o * cin + ci) * 9 + tap] * (scale ? scale[o] : 1.f);
+                        dst.push_back(f32_to_bf16_rne(v));
+                    }
+}
+
+// first layer: k = kc*16 + (lane/32)*8 + e, k < 27 -> tap = k/3, channel = k%3
+void pack_first(const float *w, const float *scale, int cout, std::vector<uint16_t> &dst)
+{
+    for (int blk = 0; blk < cout / 32; ++blk)
+        for (int kc = 0; kc < 2; ++kc)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int e = 0; e < 8; ++e) {
+                    const int o = blk * 32 + perm32(lane & 31);
+                    const int k = kc * 16 + (lane >> 5) * 8 + e;
+                    float v = 0.f;
+                    if (k < 27) v = w[((size_t)o * 3 + k % 3) * 9 + k / 3] * (scale ? scale[o] : 1.f);
+                    dst.push_back(f32_to_bf16_rne(v));
+                }
+}
+
+int default_micro_batch(const qrm_ctx *c, int h, int w)
+{
+    const size_t per_img = (size_t)h * w * c->C * 2;
+    size_t mb = ((size_t)128 << 20) / (per_img ? per_img : 1);
+    if (mb < 64) mb = 64;
+    if (mb > 8192) mb = 8192;
+    return (int)mb;
+}
+
+int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w)
+{
+    int mb = c->micro_batch > 0 ? c->micro_batch : default_micro_batch(c, h, w);
+    if ((int64_t)mb > N) mb = (int)(N > 0 ? N : 1);
+    return mb;
+}
+
+struct WsLayout {
+    size_t act, partial, symbols, total;
+    int mb, n_part;
+};
+
+WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
+{
+    WsLayout L{};
+    if (c->has_ext) {
+        L.mb = effective_micro_batch(c, N, h, w);
+        L.n_part = ((w + kTileW - 1) / kTileW) * 2;
+        L.act = align_up((size_t)L.mb * h * w * c->C * 2);
+        L.partial = align_up((size_t)L.mb * L.n_part * c->nbp * 4);
+    }
+    L.symbols = (want_symbols && c->has_rs) ? align_up((size_t)N * c->rs.n) : 0;
+    L.total = 2 * L.act + L.partial + L.symbols;
+    return L;
+}
+
+qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
+{
+    Slot *slot = nullptr;
+    for (auto &sl : c->slots)
+        if (sl.used && sl.stream == s) { slot = &sl; break; }
+    if (!slot)
+        for (auto &sl : c->slots)
+            if (!sl.used) { slot = &sl; slot->used = true; slot->stream = s; break; }
+    if (!slot) return fail(c, QRM_E_UNSUPPORTED, "more than QRM_MAX_STREAMS streams used with one context");
+    if (slot->bytes < bytes) {
+        if (slot->ws) {
+            hipError_t e = hipStreamSynchronize(s);
+            if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+            (void)hipFree(slot->ws);
+            slot->ws = nullptr;
+            slot->bytes = 0;
+        }
+        hipError_t e = hipMalloc(&slot->ws, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            char buf[128];
+            snprintf(buf, sizeof buf, "workspace allocation of %zu bytes failed", bytes);
+            return fail(c, QRM_E_NOMEM, buf);
+        }
+        slot->bytes = bytes;
+    }
+    *out = slot;
+    return QRM_OK;
+}
+
+// Runs the extractor over [N] tiles taken from `src` (whole images + origins, or raw tiles).
+// n_run < 0: full pass -> logits / bits / symbols.  n_run >= 1: stop after that many blocks -> d_act.
+qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src, int64_t N, int h, int w, int n_run,
+                         float *d_logits, uint8_t *d_bits, uint8_t *d_symbols, int m_sym, float *d_act, hipStream_t s)
+{
+    uint8_t *base = (uint8_t *)slot->ws;
+    bf16_t *buf[2] = {(bf16_t *)base, (bf16_t *)(base + L.act)};
+    float *partial = (float *)(base + 2 * L.act);
+    const int nsym = (d_symbols && m_sym > 0) ? c->n_bits / m_sym : 0;
+    const uint8_t *img0 = src.img;
+    const int32_t *off0 = src.off;
+    hipError_t e;
+    for (int64_t n0 = 0; n0 < N; n0 += L.mb) {
+        const int cnt = (int)((N - n0 < L.mb) ? (N - n0) : L.mb);
+        ConvGeom g{cnt, h, w, (h + kRows - 1) / kRows, (w + kTileW - 1) / kTileW};
+        src.img = img0 + n0 * 3 * (int64_t)src.H * src.W;
+        src.off = off0 ? off0 + 2 * n0 : nullptr;
+        int cur = 0;
+        e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, buf[cur], c->num_cu, s);
+        if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
+        const int blocks = n_run > 0 ? n_run : c->n_blocks;
+        for (int b = 1; b < blocks; ++b) {
+            hipEvent_t ev0 = nullptr, ev1 = nullptr;
+            if (c->profile) {
+                if (c->ev_used + 2 > c->ev_pool.size()) {
+                    for (int i = 0; i < 2; ++i) {
+                        hipEvent_t ev;
+                        e = hipEventCreate(&ev);
+                        if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+                        c->ev_pool.push_back(ev);
+                    }
+                }
+                ev0 = c->ev_pool[c->ev_used];
+                ev1 = c->ev_pool[c->ev_used + 1];
+                c->ev_used += 2;
+                (void)hipEventRecord(ev0, s);
+            }
+            e = launch_conv_mid(buf[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C, buf[cur ^ 1],
+                                c->num_cu, s);
+            if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
+            if (c->profile) {
+                (void)hipEventRecord(ev1, s);
+                c->prof_flops += 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
+            }
+            cur ^= 1;
+        }
+        if (n_run > 0) {
+            e = launch_nhwc_to_nchw(buf[cur], cnt, h, w, c->C, d_act + n0 * (int64_t)c->C * h * w, s);
+            if (e != hipSuccess) return hip_fail(c, e, "nhwc_to_nchw launch");
+            continue;
+        }
+        e = launch_conv_final(buf[cur], g, c->C, c->nbp, c->d_w_final, c->d_bias_final, c->final_relu, partial,
+                              c->num_cu, s);
+        if (e != hipSuccess) return hip_fail(c, e, "conv_final launch");
+        e = launch_linear_pack(partial, L.n_part, c->nbp, cnt, c->n_bits, 1.0f / ((float)h * (float)w),
+                               c->final_relu ? nullptr : c->d_bias_final, c->d_lin_w, c->d_lin_b,
+                               d_logits ? d_logits + n0 * c->n_bits : nullptr,
+                               d_bits ? d_bits + n0 * c->n_bits : nullptr,
+                               nsym ? d_symbols + n0 * nsym : nullptr, m_sym > 0 ? m_sym : 1, s);
+        if (e != hipSuccess) return hip_fail(c, e, "linear_pack launch");
+    }
+    return QRM_OK;
+}
+
+bool build_gf_tables(int m, uint32_t poly, std::vector<uint8_t> &exp2, std::vector<uint8_t> &lg)
+{
+    const int q = 1 << m, ord = q - 1;
+    exp2.assign(2 * ord, 0);
+    lg.assign(q, 0);
+    uint32_t x = 1;
+    for (int i = 0; i < ord; ++i) {
+        if (i > 0 && x == 1) return false; // alpha's order is too small: not primitive
+        exp2[i] = exp2[i + ord] = (uint8_t)x;
+        lg[x] = (uint8_t)i;
+        x <<= 1;
+        if (x & (uint32_t)q) x ^= poly;
+        if (x >= (uint32_t)q) return false; // polynomial does not have degree m
+    }
+    return x == 1;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *qrm_version(void) { return "qrm 0.1 gfx950"; }
+
+const char *qrm_last_error(const qrm_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int device, qrm_ctx **out)
+{
+    if (!out) return fail(nullptr, QRM_E_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!ext && !rs) return fail(nullptr, QRM_E_INVALID, "both descriptors are NULL");
+    if (ext) {
+        if (ext->in_ch != 3) return fail(nullptr, QRM_E_UNSUPPORTED, "in_ch must be 3");
+        if (ext->channels != 32 && ext->channels != 64) return fail(nullptr, QRM_E_INVALID, "channels must be 32 or 64");
+        if (ext->n_blocks < 1 || ext->n_blocks > 64) return fail(nullptr, QRM_E_INVALID, "n_blocks out of range");
+        if (ext->n_bits < 1 || ext->n_bits > 128) return fail(nullptr, QRM_E_INVALID, "n_bits out of range (1..128)");
+        if (!ext->conv_w || !ext->lin_w) return fail(nullptr, QRM_E_INVALID, "conv_w / lin_w is NULL");
+        if ((ext->scale == nullptr) != (ext->bias == nullptr) && ext->final_affine)
+            return fail(nullptr, QRM_E_INVALID, "final_affine needs both scale and bias");
+        for (int i = 0; i < 3; ++i)
+            if (!(ext->std[i] > 0.f)) return fail(nullptr, QRM_E_INVALID, "std must be positive");
+    }
+    std::vector<uint8_t> exp2, lg;
+    if (rs) {
+        if (rs->m < 2 || rs->m > 8) return fail(nullptr, QRM_E_INVALID, "m must be in 2..8");
+        const int q = 1 << rs->m;
+        if (rs->n > q - 1) return fail(nullptr, QRM_E_INVALID, "n exceeds 2^m - 1");
+        if (rs->k <= 0 || rs->k >= rs->n) return fail(nullptr, QRM_E_INVALID, "need 0 < k < n");
+        if ((rs->n - rs->k) & 1) return fail(nullptr, QRM_E_INVALID, "n - k must be even");
+        if (rs->fcr < 0) return fail(nullptr, QRM_E_INVALID, "fcr must be >= 0");
+        if ((rs->n - rs->k) / 2 > 8) return fail(nullptr, QRM_E_UNSUPPORTED, "t > 8 is not built");
+        if (!build_gf_tables(rs->m, rs->prim_poly, exp2, lg))
+            return fail(nullptr, QRM_E_INVALID, "prim_poly is not a primitive polynomial of degree m");
+    }
+    hipError_t e = hipSetDevice(device);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipSetDevice");
+
+    qrm_ctx *c = new qrm_ctx();
+    c->device = device;
+    int cu = 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cu > 0) c->num_cu = cu;
+
+    if (ext) {
+        const int C = ext->channels, nb = ext->n_blocks, nbits = ext->n_bits;
+        const int nbp = (nbits + 63) / 64 * 64;
+        c->has_ext = true;
+        c->n_blocks = nb; c->C = C; c->n_bits = nbits; c->nbp = nbp;
+        c->final_relu = ext->final_relu ? 1 : 0;
+        c->final_affine = (ext->final_affine && ext->scale && ext->bias) ? 1 : 0;
+        for (int i = 0; i < 3; ++i) { c->mean[i] = ext->mean[i]; c->inv_std[i] = (float)(1.0 / (double)ext->std[i]); }
+
+        std::vector<uint16_t> frag;
+        std::vector<size_t> frag_off; // element offsets: first, mids..., final
+        const float *w = ext->conv_w;
+        frag_off.push_back(frag.size());
+        pack_first(w, ext->scale, C, frag);
+        w += (size_t)C * 3 * 9;
+        for (int b = 1; b < nb; ++b) {
+            frag_off.push_back(frag.size());
+            pack_mid(w, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, C, C, frag);
+            w += (size_t)C * C * 9;
+        }
+        frag_off.push_back(frag.size());
+        pack_mid(w, c->final_affine ? ext->scale + (size_t)nb * C : nullptr, nbits, nbp, C, frag);
+
+        std::vector<float> fl; // biases [nb*C], final bias [nbp], lin_w, lin_b
+        for (int i = 0; i < nb * C; ++i) fl.push_back(ext->bias ? ext->bias[i] : 0.f);
+        const size_t off_fb = fl.size();
+        for (int i = 0; i < nbp; ++i) fl.push_back((c->final_affine && i < nbits) ? ext->bias[(size_t)nb * C + i] : 0.f);
+        const size_t off_lw = fl.size();
+        for (int i = 0; i < nbits * nbits; ++i) fl.push_back(ext->lin_w[i]);
+        const size_t off_lb = fl.size();
+        for (int i = 0; i < nbits; ++i) fl.push_back(ext->lin_b ? ext->lin_b[i] : 0.f);
+
+        const size_t frag_bytes = align_up(frag.size() * 2);
+        const size_t total = frag_bytes + align_up(fl.size() * 4);
+        e = hipMalloc(&c->d_weights, total);
+        if (e != hipSuccess) { delete c; return hip_fail(nullptr, e, "hipMalloc(weights)"); }
+        e = hipMemcpy(c->d_weights, frag.data(), frag.size() * 2, hipMemcpyHostToDevice);
+        if (e == hipSuccess)
+            e = hipMemcpy((uint8_t *)c->d_weights + frag_bytes, fl.data(), fl.size() * 4, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(c->d_weights); delete c; return hip_fail(nullptr, e, "hipMemcpy(weights)"); }
+        const bf16_t *fb = (const bf16_t *)c->d_weights;
+        c->d_w_first = fb + frag_off[0];
+        for (int b = 1; b < nb; ++b) c->d_w_mid.push_back(fb + frag_off[b]);
+        c->d_w_final = fb + frag_off[nb];
+        const float *flb = (const float *)((uint8_t *)c->d_weights + frag_bytes);
+        c->d_bias = flb;
+        c->d_bias_final = c->final_affine ? flb + off_fb : nullptr;
+        c->d_lin_w = flb + off_lw;
+        c->d_lin_b = flb + off_lb;
+    }
+    if (rs) {
+        c->has_rs = true;
+        const int q = 1 << rs->m;
+        e = hipMalloc(&c->d_tables, 1024);
+        if (e != hipSuccess) { if (c->d_weights) (void)hipFree(c->d_weights); delete c; return hip_fail(nullptr, e, "hipMalloc(tables)"); }
+        e = hipMemcpy(c->d_tables, exp2.data(), exp2.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy((uint8_t *)c->d_tables + 512, lg.data(), lg.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(c->d_tables);
+            if (c->d_weights) (void)hipFree(c->d_weights);
+            delete c;
+            return hip_fail(nullptr, e, "hipMemcpy(tables)");
+        }
+        c->rs = RsParams{rs->m, q, rs->n, rs->k, rs->n - rs->k, rs->fcr, (const uint8_t *)c->d_tables,
+                         (const uint8_t *)c->d_tables + 512};
+    }
+    *out = c;
+    return QRM_OK;
+}
+
+void qrm_destroy(qrm_ctx *c)
+{
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    for (auto &sl : c->slots)
+        if (sl.used) {
+            (void)hipStreamSynchronize(sl.stream);
+            if (sl.ws) (void)hipFree(sl.ws);
+        }
+    for (auto ev : c->ev_pool) (void)hipEventDestroy(ev);
+    if (c->d_weights) (void)hipFree(c->d_weights);
+    if (c->d_tables) (void)hipFree(c->d_tables);
+    delete c;
+}
+
+qrm_status qrm_profile_enable(qrm_ctx *c, int32_t on)
+{
+    if (!c) return QRM_E_INVALID;
+    c->profile = on != 0;
+    c->ev_used = 0;
+    c->prof_flops = 0.0;
+    return QRM_OK;
+}
+
+qrm_status qrm_profile_read(qrm_ctx *c, double *ms_total, int64_t *launches, double *flops)
+{
+    if (!c) return QRM_E_INVALID;
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
+        hipError_t e = hipEventSynchronize(c->ev_pool[i + 1]);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, c->ev_pool[i], c->ev_pool[i + 1]);
+        if (e != hipSuccess) return hip_fail(c, e, "hipEventElapsedTime");
+        ms += t;
+    }
+    if (ms_total) *ms_total = ms;
+    if (launches) *launches = (int64_t)(c->ev_used / 2);
+    if (flops) *flops = c->prof_flops;
+    c->ev_used = 0;
+    c->prof_flops = 0.0;
+    return QRM_OK;
+}
+
+qrm_status qrm_set_micro_batch(qrm_ctx *c, int32_t images)
+{
+    if (!c) return QRM_E_INVALID;
+    if (images < 0 || images > 65536) return fail(c, QRM_E_INVALID, "micro batch must be in 0..65536");
+    c->micro_batch = images;
+    return QRM_OK;
+}
+
+size_t qrm_workspace_bytes(const qrm_ctx *c, int64_t N, int32_t tile_h, int32_t tile_w)
+{
+    if (!c || N <= 0 || tile_h <= 0 || tile_w <= 0) return 0;
+    return ws_layout(c, N, tile_h, tile_w, true).total;
+}
+
+qrm_status qrm_extract_tiles(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                             const int32_t *d_off_yx, int32_t tile, uint8_t *d_tiles, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (tile <= 0 || H <= 0 || W <= 0 || tile > H || tile > W) return fail(c, QRM_E_INVALID, "need 0 < tile <= H, W");
+    if (N == 0) return QRM_OK;
+    if (!d_images || !d_tiles) return fail(c, QRM_E_INVALID, "d_images / d_tiles is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    e = launch_extract_tiles(d_images, N, H, W, d_off_yx, tile, d_tiles, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(c, e, "extract_tiles launch");
+    return QRM_OK;
+}
+
+static qrm_status extractor_common(qrm_ctx *c, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w, int n_run,
+                                   float *d_logits, uint8_t *d_bits, float *d_act, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_ext) return fail(c, QRM_E_INVALID, "context has no extractor");
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (h < 1 || w < 1 || h > 16384 || w > 16384) return fail(c, QRM_E_INVALID, "tile size out of range");
+    if (N == 0) return QRM_OK;
+    if (!d_tiles) return fail(c, QRM_E_INVALID, "d_tiles is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    hipStream_t s = (hipStream_t)stream;
+    WsLayout L = ws_layout(c, N, h, w, false);
+    Slot *slot = nullptr;
+    qrm_status st = get_slot(c, s, L.total, &slot);
+    if (st != QRM_OK) return st;
+    TileSrc src{d_tiles, nullptr, h, w, {c->mean[0], c->mean[1], c->mean[2]},
+                {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
+    return run_extractor(c, slot, L, src, N, h, w, n_run, d_logits, d_bits, nullptr, 0, d_act, s);
+}
+
+qrm_status qrm_extractor_forward(qrm_ctx *c, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w,
+                                 float *d_logits, uint8_t *d_bits, void *stream)
+{
+    if (c && N > 0 && !d_logits) return fail(c, QRM_E_INVALID, "d_logits is NULL");
+    return extractor_common(c, d_tiles, N, h, w, -1, d_logits, d_bits, nullptr, stream);
+}
+
+qrm_status qrm_extractor_blocks(qrm_ctx *c, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w, int32_t n_run,
+                                float *d_act, void *stream)
+{
+    if (c && c->has_ext && (n_run < 1 || n_run > c->n_blocks)) return fail(c, QRM_E_INVALID, "n_run out of range");
+    if (c && N > 0 && !d_act) return fail(c, QRM_E_INVALID, "d_act is NULL");
+    return extractor_common(c, d_tiles, N, h, w, n_run, nullptr, nullptr, d_act, stream);
+}
+
+qrm_status qrm_rs_decode(qrm_ctx *c, const uint8_t *d_symbols, int64_t N, uint8_t *d_msg, uint8_t *d_codeword,
+                         int8_t *d_nerr, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_rs) return fail(c, QRM_E_INVALID, "context has no Reed-Solomon code");
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (N == 0) return QRM_OK;
+    if (!d_symbols || !d_msg || !d_nerr) return fail(c, QRM_E_INVALID, "d_symbols / d_msg / d_nerr is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    e = launch_rs_decode(c->rs, d_symbols, N, d_msg, d_codeword, d_nerr, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
+    return QRM_OK;
+}
+
+qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W, const int32_t *d_off_yx,
+                      int32_t tile, float *d_logits, uint8_t *d_bits, uint8_t *d_msg, uint8_t *d_codeword,
+                      int8_t *d_nerr, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_ext || !c->has_rs) return fail(c, QRM_E_INVALID, "context needs both an extractor and a code");
+    if (c->n_bits != c->rs.n * c->rs.m) return fail(c, QRM_E_INVALID, "n_bits != n * m");
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (tile <= 0 || H <= 0 || W <= 0 || tile > H || tile > W || H > 16384 || W > 16384)
+        return fail(c, QRM_E_INVALID, "need 0 < tile <= H, W <= 16384");
+    if (N == 0) return QRM_OK;
+    if (!d_images || !d_msg || !d_nerr) return fail(c, QRM_E_INVALID, "d_images / d_msg / d_nerr is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    hipStream_t s = (hipStream_t)stream;
+    WsLayout L = ws_layout(c, N, tile, tile, true);
+    Slot *slot = nullptr;
+    qrm_status st = get_slot(c, s, L.total, &slot);
+    if (st != QRM_OK) return st;
+    uint8_t *d_sym = (uint8_t *)slot->ws + 2 * L.act + L.partial;
+    TileSrc src{d_images, d_off_yx, H, W, {c->mean[0], c->mean[1], c->mean[2]},
+                {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
+    st = run_extractor(c, slot, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, s);
+    if (st != QRM_OK) return st;
+    e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, s);
+    if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
+    return QRM_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,78 @@
+// Internal declarations shared by the HIP sources of libqrm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/qrm.h"
+
+namespace qrm {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kRows = 4;     // output rows per strip of the conv kernels
+constexpr int kTileW = 64;   // output columns per strip
+constexpr int kHaloW = kTileW + 2;
+constexpr int kMaxPart = 64; // upper bound on pooled partial sums per image handled by the linear kernel
+
+// Geometry of one extractor pass over a micro-batch.
+struct ConvGeom {
+    int n_img;      // images in this launch
+    int h, w;       // tile height / width (conv domain)
+    int strips;     // ceil(h / kRows)
+    int colblks;    // ceil(w / kTileW)
+};
+
+// Source of the first convolution: raw u8 planes of the whole image plus tile origin.
+struct TileSrc {
+    const uint8_t *img; // [N,3,H,W]
+    const int32_t *off; // [N,2] (y,x) or nullptr
+    int H, W;
+    float mean[3], inv_std[3];
+};
+
+// ---- launchers (each enqueues on `s`, returns hipGetLastError()) ----------
+
+hipError_t launch_extract_tiles(const uint8_t *img, int64_t N, int H, int W, const int32_t *off, int tile,
+                                uint8_t *out, hipStream_t s);
+
+// conv1: crop + normalise + conv3x3 (3 -> C) + bias + ReLU -> bf16 NHWC
+hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
+                             bf16_t *out, int num_cu, hipStream_t s);
+
+// conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out
+hipError_t launch_conv_mid(const bf16_t *in, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
+                           bf16_t *out, int num_cu, hipStream_t s);
+
+// final conv3x3 C -> nbp (n_bits padded to 32s) (+bias, optional ReLU) + sum over pixels -> partial sums
+// partial: f32 [n_img][colblks*2][nbp]
+hipError_t launch_conv_final(const bf16_t *in, const ConvGeom &g, int C, int nbp, const bf16_t *wfrag,
+                             const float *bias, int relu, float *partial, int num_cu, hipStream_t s);
+
+// pooled = sum(partials)/(h*w); logits = lin_w * pooled + lin_b; bits; symbols (MSB first, m bits each)
+// fbias: optional bias of the final convolution, added to the pooled value
+hipError_t launch_linear_pack(const float *partial, int n_part, int nbp, int64_t n_img, int n_bits, float inv_hw,
+                              const float *fbias, const float *lin_w, const float *lin_b, float *logits, uint8_t *bits,
+                              uint8_t *symbols, int m, hipStream_t s);
+
+// bf16 NHWC -> f32 NCHW (diagnostic)
+hipError_t launch_nhwc_to_nchw(const bf16_t *in, int64_t n_img, int h, int w, int C, float *out, hipStream_t s);
+
+struct RsParams {
+    int m, q, n, k, two_t, fcr;
+    const uint8_t *exp2; // device, [2*(q-1)] alpha^i
+    const uint8_t *log;  // device, [q], log[0] unused
+};
+
+hipError_t launch_rs_decode(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
+                            hipStream_t s);
+
+// host-side helpers
+uint16_t f32_to_bf16_rne(float f);
+
+} // namespace qrm

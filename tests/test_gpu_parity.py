@@ -1,0 +1,362 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bit-exact for tile crops, symbols and Reed-Solomon outputs; extractor logits within
+2e-2 * max(1, |ref|) and hard bits equal wherever |oracle logit| > 1e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import dev, empty, check_logits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qrm():
+    import paper_2509_02447_amd as q
+    return q
+
+
+def rs_dict(cfg):
+    return dict(m=cfg.m, prim_poly=cfg.prim_poly, n=cfg.n, k=cfg.k, fcr=cfg.fcr)
+
+
+# ---------------------------------------------------------------- Reed-Solomon
+
+def gpu_rs_decode(ctx, words, want_cw=True):
+    N, n = words.shape
+    d_sym = dev(words)
+    d_msg = empty((N, ctx.k), torch.uint8)
+    d_cw = empty((N, n), torch.uint8) if want_cw else None
+    d_ne = empty((N,), torch.int8)
+    ctx.qrm_rs_decode(d_sym, N, d_msg, d_cw, d_ne)
+    torch.cuda.synchronize()
+    return d_msg.cpu().numpy(), (d_cw.cpu().numpy() if want_cw else None), d_ne.cpu().numpy()
+
+
+RS_CASES = [
+    ("C1 rs(15,11) gf16", dict(m=4, prim_poly=0x13, n=15, k=11, fcr=1), 0, 1024),
+    ("C2 rs(12,8) gf16", dict(m=4, prim_poly=0x13, n=12, k=8, fcr=1), 1, 4099),
+    ("C4 rs(12,8) gf256", dict(m=8, prim_poly=0x11D, n=12, k=8, fcr=1), 3, 5000),
+    ("rs(16,12) gf256 fcr0", dict(m=8, prim_poly=0x11D, n=16, k=12, fcr=0), 5, 777),
+    ("rs(20,14) gf256 t3", dict(m=8, prim_poly=0x11D, n=20, k=14, fcr=1), 6, 1001),
+    ("rs(63,55) gf64 t4", dict(m=6, prim_poly=0x43, n=63, k=55, fcr=1), 7, 513),
+    ("rs(100,84) gf256 t8", dict(m=8, prim_poly=0x11D, n=100, k=84, fcr=1), 8, 300),
+    ("rs(255,239) gf256 t8", dict(m=8, prim_poly=0x11D, n=255, k=239, fcr=1), 9, 200),
+    ("rs(7,3) gf8", dict(m=3, prim_poly=0xB, n=7, k=3, fcr=1), 10, 640),
+]
+
+
+@pytest.mark.parametrize("name,code,cfg_index,count", RS_CASES, ids=[c[0] for c in RS_CASES])
+def test_rs_decode_bit_exact(qrm, name, code, cfg_index, count):
+    t = (code["n"] - code["k"]) // 2
+    msgs, err, ninj = synth.rs_cases(cfg_index, count, code["n"], code["k"], code["m"], max_err=t + 1)
+    clean = oracle.rs_encode(msgs, **code)
+    words = clean ^ err
+    rand = synth.random_words(cfg_index, count // 2 + 1, code["n"], code["m"])
+    allw = np.concatenate([words, rand, clean[:5]], axis=0)
+    ctx = qrm.Context(rs=code)
+    gm, gc, ge = gpu_rs_decode(ctx, allw)
+    om, oc, oe = oracle.rs_decode(allw, **code)
+    assert np.array_equal(ge, oe), f"{name}: nerr differs at {np.nonzero(ge != oe)[0][:10]}"
+    assert np.array_equal(gm, om) and np.array_equal(gc, oc)
+    # and the guarantees themselves, on the GPU output
+    ok = ninj <= t
+    assert np.array_equal(gm[:count][ok], msgs[ok]) and np.array_equal(ge[:count][ok], ninj[ok].astype(np.int8))
+    # without the optional codeword output
+    gm2, _, ge2 = gpu_rs_decode(ctx, allw, want_cw=False)
+    assert np.array_equal(gm2, gm) and np.array_equal(ge2, ge)
+    print(f"[parity] {name}: {allw.shape[0]} words bit-exact, failures flagged: {(ge < 0).sum()}")
+    ctx.close()
+
+
+@pytest.mark.parametrize("N", [1, 3, 4, 5, 63, 64, 65])
+def test_rs_decode_small_batches(qrm, N):
+    code = dict(m=4, prim_poly=0x13, n=15, k=11, fcr=1)
+    msgs, err, _ = synth.rs_cases(0, N, 15, 11, 4, block=N)
+    words = oracle.rs_encode(msgs, **code) ^ err
+    ctx = qrm.Context(rs=code)
+    gm, gc, ge = gpu_rs_decode(ctx, words)
+    om, oc, oe = oracle.rs_decode(words, **code)
+    assert np.array_equal(ge, oe) and np.array_equal(gm, om) and np.array_equal(gc, oc)
+    ctx.close()
+
+
+def test_rs_decode_full_size_sets(qrm):
+    """The two stand-alone codeword sets at their full sizes: 1024 x RS(15,11)/GF(16) and
+    2^20 x RS(12,8)/GF(256), 0..3 random symbol errors."""
+    for cfg in (synth.CONFIGS["C1"], synth.CONFIGS["C4"]):
+        code = rs_dict(cfg)
+        msgs, err, ninj = synth.rs_cases(cfg.index, cfg.n_codewords, cfg.n, cfg.k, cfg.m)
+        words = oracle.rs_encode(msgs, **code) ^ err
+        ctx = qrm.Context(rs=code)
+        gm, gc, ge = gpu_rs_decode(ctx, words)
+        om, oc, oe = oracle.rs_decode(words, **code)
+        assert np.array_equal(ge, oe) and np.array_equal(gm, om) and np.array_equal(gc, oc)
+        ok = ninj <= cfg.t
+        assert np.array_equal(gm[ok], msgs[ok])
+        print(f"[parity] {cfg.name} codeword set: {cfg.n_codewords} words bit-exact")
+        ctx.close()
+
+
+def test_rs_symbols_above_field_are_masked(qrm):
+    code = dict(m=4, prim_poly=0x13, n=12, k=8, fcr=1)
+    msgs, err, _ = synth.rs_cases(1, 100, 12, 8, 4)
+    words = oracle.rs_encode(msgs, **code) ^ err
+    ctx = qrm.Context(rs=code)
+    a = gpu_rs_decode(ctx, words)
+    b = gpu_rs_decode(ctx, words | 0xF0)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    ctx.close()
+
+
+# ---------------------------------------------------------------- tile crop
+
+@pytest.mark.parametrize("N,H,W,tile", [(16, 256, 256, 32), (33, 256, 256, 64), (5, 100, 117, 30),
+                                        (4, 64, 64, 64), (7, 50, 90, 17), (3, 512, 512, 128)])
+def test_extract_tiles_bit_exact(qrm, N, H, W, tile):
+    rng = np.random.default_rng(N * 1000 + tile)
+    imgs = rng.integers(0, 256, size=(N, 3, H, W), dtype=np.uint8)
+    off = np.stack([rng.integers(-3, H - tile + 4, size=N), rng.integers(-3, W - tile + 4, size=N)], 1).astype(np.int32)
+    off[0] = (0, 0)
+    off[-1] = (H - tile, W - tile)
+    ctx = qrm.Context(rs=dict(m=4, prim_poly=0x13, n=15, k=11))
+    d_t = empty((N, 3, tile, tile), torch.uint8)
+    ctx.qrm_extract_tiles(dev(imgs), N, H, W, dev(off), tile, d_t)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_t.cpu().numpy(), oracle.extract_tiles(imgs, off, tile))
+    d_t.zero_()
+    ctx.qrm_extract_tiles(dev(imgs), N, H, W, None, tile, d_t)       # NULL offsets = top-left ("fixed")
+    torch.cuda.synchronize()
+    assert np.array_equal(d_t.cpu().numpy(), oracle.extract_tiles(imgs, None, tile))
+    ctx.close()
+
+
+# ---------------------------------------------------------------- extractor
+
+def small_weights(C, nb, nbits, seed):
+    return synth.extractor_weights(3, nb, C, nbits, seed_index=200 + seed)
+
+
+@pytest.mark.parametrize("C,nb,h,w", [(32, 3, 32, 32), (64, 3, 16, 64), (64, 2, 21, 70), (32, 2, 9, 33),
+                                      (64, 2, 4, 130)])
+def test_extractor_blocks_match_oracle_layer_by_layer(qrm, C, nb, h, w):
+    wts = small_weights(C, nb, 16, C + nb)
+    rng = np.random.default_rng(h * w)
+    tiles = rng.integers(0, 256, size=(2, 3, h, w), dtype=np.uint8)
+    ctx = qrm.Context(weights=wts)
+    refs = [oracle.extractor_forward(wts, tiles[i:i + 1], want_acts=True)[2] for i in range(2)]
+    for b in range(1, nb + 1):
+        d_act = empty((2, C, h, w), torch.float32)
+        ctx.qrm_extractor_blocks(dev(tiles), 2, h, w, b, d_act)
+        torch.cuda.synchronize()
+        got = d_act.cpu().numpy().astype(np.float64)
+        for i in range(2):
+            ref = refs[i][b - 1]
+            err = np.abs(got[i] - ref) / np.maximum(1.0, np.abs(ref))
+            print(f"[parity] C={C} {h}x{w} block {b} image {i}: max scaled activation error {err.max():.3e}")
+            # bf16 operands (inputs and weights, relative step 2^-9 each) and one bf16 rounding per layer:
+            # an element of size ~1 built from 27..576 products carries noise of a few 1e-3; the maximum
+            # over ~1e5 elements sits near 2e-2.  A wrong tap, channel or halo is an O(1) error.
+            rms = float(np.sqrt(np.mean((got[i] - ref) ** 2)))
+            assert err.max() <= 0.05 and rms <= 0.004 * b + 0.006, (b, i, float(err.max()), rms,
+                                                                     np.unravel_index(err.argmax(), err.shape))
+    ctx.close()
+
+
+EXT_CASES = [
+    ("C1 shape 32x32 c32 b4 60bit", 32, 4, 60, 32, 32, 16),
+    ("C2 shape 64x64 c64 b8 48bit", 64, 8, 48, 64, 64, 6),
+    ("C4 shape 128x128 c64 b8 96bit", 64, 8, 96, 128, 128, 2),
+    ("ragged 48x80 c64 b3 48bit", 64, 3, 48, 48, 80, 5),
+    ("ragged 30x30 c32 b2 60bit", 32, 2, 60, 30, 30, 9),
+    ("tiny 5x7 c64 b2 8bit", 64, 2, 8, 5, 7, 3),
+]
+
+
+@pytest.mark.parametrize("name,C,nb,nbits,h,w,N", EXT_CASES, ids=[c[0] for c in EXT_CASES])
+def test_extractor_forward_logits_and_bits(qrm, name, C, nb, nbits, h, w, N):
+    wts = small_weights(C, nb, nbits, nb * 7 + nbits)
+    rng = np.random.default_rng(nbits + h)
+    tiles = rng.integers(0, 256, size=(N, 3, h, w), dtype=np.uint8)
+    ref_logits, _ = oracle.extractor_forward(wts, tiles)
+    ctx = qrm.Context(weights=wts)
+    ctx.qrm_set_micro_batch(4)                     # several micro-batches and a ragged last one
+    d_logits, d_bits = empty((N, nbits), torch.float32), empty((N, nbits), torch.uint8)
+    ctx.qrm_extractor_forward(dev(tiles), N, h, w, d_logits, d_bits)
+    torch.cuda.synchronize()
+    check_logits(d_logits.cpu().numpy(), ref_logits, d_bits.cpu().numpy(), what=name)
+    ctx.close()
+
+
+def test_extractor_final_relu_and_affine(qrm):
+    wts = small_weights(64, 2, 48, 99)
+    g = np.random.default_rng(9)
+    wts["scale"] = np.concatenate([wts["scale"], g.normal(1, 0.1, 48).astype(np.float32)])
+    wts["bias"] = np.concatenate([wts["bias"], g.normal(0, 0.1, 48).astype(np.float32)])
+    tiles = g.integers(0, 256, size=(3, 3, 20, 40), dtype=np.uint8)
+    for relu in (0, 1):
+        ref, _ = oracle.extractor_forward(wts, tiles, final_relu=relu)
+        ctx = qrm.Context(weights=wts, final_relu=relu)
+        d_logits = empty((3, 48), torch.float32)
+        ctx.qrm_extractor_forward(dev(tiles), 3, 20, 40, d_logits, None)
+        torch.cuda.synchronize()
+        check_logits(d_logits.cpu().numpy(), ref, what=f"final affine, relu={relu}")
+        ctx.close()
+
+
+# ---------------------------------------------------------------- whole path
+
+def run_detect(ctx, cfg, imgs, off, want_all=True):
+    N = imgs.shape[0]
+    d_logits = empty((N, cfg.n_bits), torch.float32) if want_all else None
+    d_bits = empty((N, cfg.n_bits), torch.uint8) if want_all else None
+    d_msg, d_cw, d_ne = empty((N, cfg.k), torch.uint8), empty((N, cfg.n), torch.uint8), empty((N,), torch.int8)
+    ctx.qrm_detect(dev(imgs), N, cfg.H, cfg.W, None if off is None else dev(off), cfg.tile,
+                   d_logits, d_bits, d_msg, d_cw if want_all else None, d_ne)
+    torch.cuda.synchronize()
+    out = dict(msg=d_msg.cpu().numpy(), nerr=d_ne.cpu().numpy())
+    if want_all:
+        out.update(logits=d_logits.cpu().numpy(), bits=d_bits.cpu().numpy(), codeword=d_cw.cpu().numpy())
+    return out
+
+
+def check_detect(cfg, wts, imgs, off, got, what):
+    ref = oracle.detect(wts, imgs, off, cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    check_logits(got["logits"], ref["logits"], got["bits"], what=what)
+    # RS outputs are bit-exact given identical hard bits: decode the GPU's own bits with the oracle
+    syms = oracle.bits_to_symbols(got["bits"], cfg.m)
+    om, oc, oe = oracle.rs_decode(syms, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    assert np.array_equal(got["msg"], om) and np.array_equal(got["codeword"], oc) and np.array_equal(got["nerr"], oe)
+    if np.array_equal(got["bits"], ref["bits"]):
+        assert np.array_equal(got["msg"], ref["msg"]) and np.array_equal(got["nerr"], ref["nerr"])
+
+
+def test_detect_config_c1_every_image(qrm):
+    cfg = synth.CONFIGS["C1"]
+    wts = synth.config_weights(cfg)
+    imgs, off = synth.images(cfg, 0, cfg.n_images), synth.offsets(cfg, 0, cfg.n_images)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    got = run_detect(ctx, cfg, imgs, off)
+    check_detect(cfg, wts, imgs, off, got, "C1 detect, 16 images")
+    lean = run_detect(ctx, cfg, imgs, off, want_all=False)           # optional outputs NULL
+    assert np.array_equal(lean["msg"], got["msg"]) and np.array_equal(lean["nerr"], got["nerr"])
+    ctx.close()
+
+
+@pytest.mark.parametrize("policy", ["random", "random_grid", "fixed"])
+def test_detect_config_c2_sample(qrm, policy):
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = 12
+    imgs, off = synth.images(cfg, 100, N), synth.offsets(cfg, 100, N, policy)
+    if policy == "random":
+        off[0] = (0, 0); off[1] = (cfg.H - cfg.tile, cfg.W - cfg.tile); off[2] = (-7, 400)   # clamped
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    ctx.qrm_set_micro_batch(5)
+    got = run_detect(ctx, cfg, imgs, off)
+    check_detect(cfg, wts, imgs, off, got, f"C2 detect ({policy}), {N} images")
+    ctx.close()
+
+
+def test_detect_config_c4_sample(qrm):
+    cfg = synth.CONFIGS["C4"]
+    wts = synth.config_weights(cfg)
+    N = 3
+    imgs, off = synth.images(cfg, 7, N), synth.offsets(cfg, 7, N)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    got = run_detect(ctx, cfg, imgs, off)
+    check_detect(cfg, wts, imgs, off, got, f"C4 detect, {N} images")
+    ctx.close()
+
+
+def test_detect_config_c3_one_image(qrm):
+    cfg = synth.CONFIGS["C3"]
+    wts = synth.config_weights(cfg)
+    imgs = synth.images(cfg, 3, 1)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    got = run_detect(ctx, cfg, imgs, None)
+    check_detect(cfg, wts, imgs, None, got, "C3 detect (untiled 256x256), 1 image")
+    ctx.close()
+
+
+def test_detect_equals_separate_calls(qrm):
+    """qrm_detect == qrm_extract_tiles -> qrm_extractor_forward -> (pack) -> qrm_rs_decode, bit for bit."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = 9
+    imgs, off = synth.images(cfg, 50, N), synth.offsets(cfg, 50, N)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    got = run_detect(ctx, cfg, imgs, off)
+    d_tiles = empty((N, 3, cfg.tile, cfg.tile), torch.uint8)
+    ctx.qrm_extract_tiles(dev(imgs), N, cfg.H, cfg.W, dev(off), cfg.tile, d_tiles)
+    d_logits, d_bits = empty((N, cfg.n_bits), torch.float32), empty((N, cfg.n_bits), torch.uint8)
+    ctx.qrm_extractor_forward(d_tiles, N, cfg.tile, cfg.tile, d_logits, d_bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_logits.cpu().numpy(), got["logits"]) and np.array_equal(d_bits.cpu().numpy(), got["bits"])
+    syms = oracle.bits_to_symbols(d_bits.cpu().numpy(), cfg.m)
+    gm, gc, ge = gpu_rs_decode(ctx, syms)
+    assert np.array_equal(gm, got["msg"]) and np.array_equal(gc, got["codeword"]) and np.array_equal(ge, got["nerr"])
+    ctx.close()
+
+
+def test_detect_on_two_streams(qrm):
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = 8
+    imgs, off = synth.images(cfg, 300, 2 * N), synth.offsets(cfg, 300, 2 * N)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    base = run_detect(ctx, cfg, imgs, off)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    d_img, d_off = dev(imgs), dev(off)
+    outs = []
+    torch.cuda.synchronize()
+    for i, s in enumerate((s1, s2)):
+        d_logits = empty((N, cfg.n_bits), torch.float32)
+        d_msg, d_ne = empty((N, cfg.k), torch.uint8), empty((N,), torch.int8)
+        ctx.qrm_detect(d_img[i * N:(i + 1) * N], N, cfg.H, cfg.W, d_off[i * N:(i + 1) * N], cfg.tile,
+                       d_logits, None, d_msg, None, d_ne, stream=s)
+        outs.append((d_logits, d_msg, d_ne))
+    torch.cuda.synchronize()
+    for i, (l, m_, e) in enumerate(outs):
+        assert np.array_equal(l.cpu().numpy(), base["logits"][i * N:(i + 1) * N])
+        assert np.array_equal(m_.cpu().numpy(), base["msg"][i * N:(i + 1) * N])
+        assert np.array_equal(e.cpu().numpy(), base["nerr"][i * N:(i + 1) * N])
+    ctx.close()
+
+
+# ---------------------------------------------------------------- error paths (host side only)
+
+def test_error_statuses(qrm):
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    with pytest.raises(qrm.QrmError) as e:
+        qrm.Context(rs=dict(m=4, prim_poly=0x13, n=16, k=12))
+    assert e.value.status == qrm.QRM_E_INVALID
+    with pytest.raises(qrm.QrmError):
+        qrm.Context(rs=dict(m=4, prim_poly=0x13, n=15, k=12))          # odd n - k
+    with pytest.raises(qrm.QrmError):
+        qrm.Context(rs=dict(m=4, prim_poly=0x1F, n=15, k=11))          # not primitive
+    with pytest.raises(qrm.QrmError) as e:
+        qrm.Context(rs=dict(m=8, prim_poly=0x11D, n=255, k=235))       # t = 10
+    assert e.value.status == qrm.QRM_E_UNSUPPORTED
+    ctx = qrm.Context(weights=wts, rs=dict(m=4, prim_poly=0x13, n=15, k=11))   # 48 bits != 60
+    d_img = empty((2, 3, 256, 256), torch.uint8)
+    d_msg, d_ne = empty((2, 11), torch.uint8), empty((2,), torch.int8)
+    with pytest.raises(qrm.QrmError) as e:
+        ctx.qrm_detect(d_img, 2, 256, 256, None, 64, None, None, d_msg, None, d_ne)
+    assert e.value.status == qrm.QRM_E_INVALID and "n_bits" in e.value.message
+    with pytest.raises(qrm.QrmError):
+        ctx.qrm_extract_tiles(d_img, 2, 256, 256, None, 300, d_img)    # tile > H
+    with pytest.raises(qrm.QrmError):
+        ctx.qrm_rs_decode(None, 4, d_msg, None, d_ne)                  # NULL symbols
+    ctx.qrm_rs_decode(None, 0, None, None, None)                       # N == 0 is a no-op
+    rs_only = qrm.Context(rs=dict(m=4, prim_poly=0x13, n=15, k=11))
+    with pytest.raises(qrm.QrmError):
+        rs_only.qrm_extractor_forward(d_img, 2, 256, 256, empty((2, 48), torch.float32))
+    rs_only.close()
+    ctx.close()
