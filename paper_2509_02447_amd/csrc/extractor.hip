@@ -42,89 +42,163 @@ __device__ __forceinline__ int xcd_virtual_block(int b, int nblocks)
     return (b % 8) * (nblocks / 8) + b / 8;
 }
 
-// lane (px, half) holds 16 consecutive channels [half*16, half*16+16) of the 32-channel block
-__device__ __forceinline__ void store_tile_bf16(bf16_t *dst, const f32x16 &acc, const float *bias16, bool relu)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 (round to nearest even) with ReLU applied on the packed pair: a negative bf16
+// has its sign bit set, i.e. is negative as a 16-bit integer, so max(.,0) on the halves clamps it.
+__device__ __forceinline__ uint32_t pack_bf16_relu(float a, float b, bool relu)
 {
-    bf16x8 lo, hi;
+    bf16x2 p = {(bf16_t)a, (bf16_t)b};
+    s16x2 q = __builtin_bit_cast(s16x2, p);
+    if (relu) q = __builtin_elementwise_max(q, (s16x2){0, 0});
+    return __builtin_bit_cast(uint32_t, q);
+}
+
+// lane (px, half) holds 16 consecutive channels [half*16, half*16+16) of the 32-channel block
+__device__ __forceinline__ void store_tile_bf16(bf16_t *dst, const f32x16 &acc, bool relu)
+{
+    u32x4 lo, hi;
 #pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        float a = acc[v] + bias16[v];
-        float b = acc[v + 8] + bias16[v + 8];
-        if (relu) { a = fmaxf(a, 0.f); b = fmaxf(b, 0.f); }
-        lo[v] = (bf16_t)a;
-        hi[v] = (bf16_t)b;
+    for (int v = 0; v < 4; ++v) {
+        lo[v] = pack_bf16_relu(acc[2 * v], acc[2 * v + 1], relu);
+        hi[v] = pack_bf16_relu(acc[8 + 2 * v], acc[8 + 2 * v + 1], relu);
     }
-    *(bf16x8 *)dst = lo;
-    *(bf16x8 *)(dst + 8) = hi;
+    *(u32x4 *)dst = lo;
+    *(u32x4 *)(dst + 8) = hi;
 }
 
 // ------------------------------------------------------------------------------------------------
-// conv3x3 C -> C (+bias, ReLU), bf16 NHWC in / out.  One strip = kRows x kTileW output pixels.
-// MODE 0: write activations.  MODE 1: final layer, accumulate the pixel sum (no ReLU).
+// conv3x3 C -> C on bf16 NHWC activations.  One strip = kRows x kTileW output pixels.
 // ------------------------------------------------------------------------------------------------
 template <int C>
 struct MidCfg {
-    static constexpr int KC = C / 16;           // 16-channel k chunks per tap
-    static constexpr int NCB = C / 32;          // 32-wide output channel blocks
-    static constexpr int PS = C * 2 + 16;       // LDS bytes per pixel (padded)
-    static constexpr int LDS_BYTES = (kRows + 2) * kHaloW * PS;
-    static constexpr int CHUNKS = (kRows + 2) * kHaloW * (C / 8); // 16-byte pieces per strip
+    static constexpr int KC = C / 16;                 // 16-channel k chunks per tap
+    static constexpr int NCB = C / 32;                // 32-wide output channel blocks
+    static constexpr int PS = C * 2 + 16;             // LDS bytes per pixel: C bf16 + one 16-byte pad slot
+    static constexpr int SPP = PS / 16;               // 16-byte slots per pixel
+    static constexpr int ROW_SLOTS = kHaloW * SPP;    // slots of one staged row (halo columns included)
+    static constexpr int PIECES = (ROW_SLOTS + 63) / 64; // wavefront-wide direct-to-LDS loads per row
+    static constexpr int ROWB = PIECES * 1024;        // LDS bytes per staged row
+    static constexpr int LDS_BYTES = (kRows + 2) * ROWB;
+    static constexpr int QPW = (PIECES + 3) / 4;      // pieces of a row one wavefront is responsible for
 };
 
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// Asynchronous staging of one strip (kRows + 2 rows, halo included) into LDS with direct-to-LDS loads.
+// A staged row is cut into PIECES pieces of 64 slots of 16 bytes; one wavefront-wide load fills one
+// piece (1 KiB of LDS at row*ROWB + piece*1024), lane l supplying slot piece*64 + l = (column, 8-channel
+// chunk).  Wavefront w always handles pieces w, w+4, ..., so the per-lane column decoding is done once
+// per strip, not once per load.  Pad slots and pixels outside the tile read from the block of zeros
+// that opens the workspace (offset 0 from `ws`): that is the zero padding of the convolution.  All
+// sources are addressed as ws + 32-bit byte offset.  The caller waits with s_waitcnt vmcnt(0) and a
+// barrier before reading the strip.
 template <int C>
-__device__ __forceinline__ void stage_strip(uint8_t *lds, const bf16_t *__restrict__ in, int64_t img_base, int h,
-                                            int w, int y0, int x0, int tid)
+__device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *ws, uint32_t img_off, int h, int w,
+                                                  int y0, int x0, int wave, int lane)
 {
     typedef MidCfg<C> K;
-    constexpr int IT = (K::CHUNKS + 255) / 256;
-    u32x4 v[IT];
+    uint32_t coff[K::QPW]; // byte offset of this lane's slot inside an image row, or ~0u for "zeros"
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
-        const int idx = tid + it * 256;
-        const int c8 = idx % (C / 8);
-        const int pc = idx / (C / 8);
-        const int col = pc % kHaloW, row = pc / kHaloW;
-        const int gy = y0 - 1 + row, gx = x0 - 1 + col;
-        v[it] = (u32x4){0u, 0u, 0u, 0u};
-        if (idx < K::CHUNKS && gy >= 0 && gy < h && gx >= 0 && gx < w)
-            v[it] = *(const u32x4 *)(in + (img_base + (int64_t)gy * w + gx) * C + c8 * 8);
+    for (int qi = 0; qi < K::QPW; ++qi) {
+        const int slot = (wave + 4 * qi) * 64 + lane;
+        const int col = slot / K::SPP, cpos = slot - col * K::SPP;
+        const int gx = x0 - 1 + col;
+        const bool ok = cpos < C / 8 && col < kHaloW && gx >= 0 && gx < w;
+        coff[qi] = ok ? (uint32_t)((gx * C + cpos * 8) * 2) : ~0u;
     }
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
-        const int idx = tid + it * 256;
-        const int c8 = idx % (C / 8);
-        const int pc = idx / (C / 8);
-        if (idx < K::CHUNKS) *(u32x4 *)(lds + pc * K::PS + c8 * 16) = v[it];
+    for (int r = 0; r < kRows + 2; ++r) {
+        const int gy = y0 - 1 + r;                                  // same for the whole workgroup
+        const bool rowok = gy >= 0 && gy < h;
+        const uint32_t rowoff = img_off + (uint32_t)(gy * w * C * 2);
+#pragma unroll
+        for (int qi = 0; qi < K::QPW; ++qi) {
+            const int q = wave + 4 * qi;                            // same for the whole wavefront
+            if (q < K::PIECES) {
+                const uint32_t off = (rowok && coff[qi] != ~0u) ? rowoff + coff[qi] : 0u;
+                __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + r * K::ROWB + q * 1024), 16, 0, 0);
+            }
+        }
+    }
+}
+
+// Accumulates RW output rows of one 32-pixel x 32-channel block from the staged strip.  Fragments are
+// read one (input row, horizontal tap) group ahead of the matrix instructions that consume them; each
+// fragment feeds the up to three vertical taps that touch its input row.
+// POOL: all rows are summed into acc[0] / acc[1] (global average pool of the last layer); rows at or
+// beyond `rows_valid` are skipped (RAGGED: the last strip of a tile whose height is not a multiple of kRows).
+template <int C, int RW, bool POOL, bool RAGGED = false>
+__device__ __forceinline__ void strip_mma(const uint8_t *lbase, const bf16x8 (&Wr)[9][C / 16], f32x16 *acc,
+                                          int rows_valid)
+{
+    typedef MidCfg<C> K;
+    constexpr int NG = (RW + 2) * 3;
+    bf16x8 f[2][K::KC];
+#pragma unroll
+    for (int kc = 0; kc < K::KC; ++kc) f[0][kc] = *(const bf16x8 *)(lbase + kc * 32);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const int r = g / 3, dx = g % 3;
+        if (g + 1 < NG) {
+            const int r2 = (g + 1) / 3, dx2 = (g + 1) % 3;
+#pragma unroll
+            for (int kc = 0; kc < K::KC; ++kc)
+                f[(g + 1) & 1][kc] = *(const bf16x8 *)(lbase + r2 * K::ROWB + dx2 * K::PS + kc * 32);
+        }
+#pragma unroll
+        for (int kc = 0; kc < K::KC; ++kc) {
+#pragma unroll
+            for (int dy = 0; dy < 3; ++dy) {
+                const int orow = r - dy;
+                if (orow >= 0 && orow < RW) {
+                    if (POOL) {
+                        if (!RAGGED || orow < rows_valid)
+                            acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], f[g & 1][kc], acc[orow & 1]);
+                    } else {
+                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[g & 1][kc], acc[orow]);
+                    }
+                }
+            }
+        }
     }
 }
 
 template <int C>
-__global__ __launch_bounds__(256, 2) void conv_mid_kernel(const bf16_t *__restrict__ in, ConvGeom g,
-                                                          const bf16_t *__restrict__ wfrag,
+__device__ __forceinline__ void load_weight_frags(bf16x8 (&Wr)[9][C / 16], const bf16_t *wfrag, int blk, int lane)
+{
+    typedef MidCfg<C> K;
+    const bf16x8 *wp = (const bf16x8 *)wfrag + (int64_t)blk * 9 * K::KC * 64 + lane;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int kc = 0; kc < K::KC; ++kc) Wr[tap][kc] = wp[(tap * K::KC + kc) * 64];
+}
+
+// C -> C (+bias, ReLU), bf16 NHWC in / out.  Two workgroups per CU: while one waits for its strip to
+// land in LDS the other keeps the matrix cores busy.
+template <int C>
+__global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
+                                                          ConvGeom g, const bf16_t *__restrict__ wfrag,
                                                           const float *__restrict__ bias, bf16_t *__restrict__ out)
 {
     typedef MidCfg<C> K;
     constexpr int RG = 2 / K::NCB;     // row groups among the 4 wavefronts
     constexpr int RW = kRows / RG;     // output rows per wavefront
-    __shared__ __attribute__((aligned(16))) uint8_t lds[K::LDS_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[K::LDS_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int px = lane & 31, half = lane >> 5;
     const int cb = wave % K::NCB;
     const int xb = (wave / K::NCB) & 1;
     const int rg = wave / (K::NCB * 2);
 
     bf16x8 Wr[9][K::KC];
-    {
-        const bf16x8 *wp = (const bf16x8 *)wfrag + (int64_t)cb * 9 * K::KC * 64 + lane;
-#pragma unroll
-        for (int tap = 0; tap < 9; ++tap)
-#pragma unroll
-            for (int kc = 0; kc < K::KC; ++kc) Wr[tap][kc] = wp[(tap * K::KC + kc) * 64];
-    }
-    float bias16[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) bias16[v] = 0.f;
+    load_weight_frags<C>(Wr, wfrag, cb, lane);
+    const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
 
     const int total = g.n_img * g.strips * g.colblks;
     const int nb = gridDim.x;
@@ -132,54 +206,55 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const bf16_t *__restri
     const int per = (total + nb - 1) / nb;
     const int t_begin = vb * per;
     const int t_end = min(total, t_begin + per);
+    const uint8_t *lbase = lds + (rg * RW) * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
 
-    for (int t = t_begin; t < t_end; ++t) {
+    auto decode = [&](int t, int &n, int &y0, int &x0) {
         const int colblk = t % g.colblks;
         const int strip = (t / g.colblks) % g.strips;
-        const int n = t / (g.colblks * g.strips);
-        const int y0 = strip * kRows, x0 = colblk * kTileW;
-        const int64_t img_base = (int64_t)n * g.h * g.w;
+        n = t / (g.colblks * g.strips);
+        y0 = strip * kRows;
+        x0 = colblk * kTileW;
+    };
 
-        __syncthreads(); // everyone is done reading the previous strip
-        stage_strip<C>(lds, in, img_base, g.h, g.w, y0, x0, tid);
-        __syncthreads();
+    if (t_begin < t_end) {
+        int n, y0, x0;
+        decode(t_begin, n, y0, x0);
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, y0, x0, wave,
+                             lane);
+    }
+    for (int t = t_begin; t < t_end; ++t) {
+        int n, y0, x0;
+        decode(t, n, y0, x0);
 
+        // accumulators start from the bias (16 consecutive channels per lane)
         f32x16 acc[RW];
-#pragma unroll
-        for (int r = 0; r < RW; ++r)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[r][v] = 0.f;
-
-        const uint8_t *lbase = lds + ((rg * RW) * kHaloW + xb * 32 + px) * K::PS + half * 16;
-#pragma unroll
-        for (int r = 0; r < RW + 2; ++r) {
-#pragma unroll
-            for (int dx = 0; dx < 3; ++dx) {
-#pragma unroll
-                for (int kc = 0; kc < K::KC; ++kc) {
-                    const bf16x8 b = *(const bf16x8 *)(lbase + (r * kHaloW + dx) * K::PS + kc * 32);
-#pragma unroll
-                    for (int dy = 0; dy < 3; ++dy) {
-                        const int orow = r - dy;
-                        if (orow >= 0 && orow < RW) acc[orow] = mfma32(Wr[dy * 3 + dx][kc], b, acc[orow]);
-                    }
-                }
-            }
-        }
-
-        const int x = x0 + xb * 32 + px;
-        const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 bq = bp[q];
-            bias16[4 * q] = bq.x; bias16[4 * q + 1] = bq.y; bias16[4 * q + 2] = bq.z; bias16[4 * q + 3] = bq.w;
+#pragma unroll
+            for (int r = 0; r < RW; ++r) {
+                acc[r][4 * q] = bq.x; acc[r][4 * q + 1] = bq.y; acc[r][4 * q + 2] = bq.z; acc[r][4 * q + 3] = bq.w;
+            }
         }
+
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads(); // the strip has landed for every wavefront
+        strip_mma<C, RW, false>(lbase, Wr, acc, RW);
+        __syncthreads(); // everyone is done reading: the buffer may be refilled
+        if (t + 1 < t_end) {
+            int n2, y2, x2;
+            decode(t + 1, n2, y2, x2);
+            issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n2 * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, y2, x2,
+                                 wave, lane);
+        }
+
+        const int x = x0 + xb * 32 + px;
+        const int64_t img_base = (int64_t)n * g.h * g.w;
 #pragma unroll
         for (int r = 0; r < RW; ++r) {
             const int y = y0 + rg * RW + r;
             if (y < g.h && x < g.w)
-                store_tile_bf16(out + (img_base + (int64_t)y * g.w + x) * C + cb * 32 + half * 16, acc[r], bias16,
-                                true);
+                store_tile_bf16(out + (img_base + (int64_t)y * g.w + x) * C + cb * 32 + half * 16, acc[r], true);
         }
     }
 }
@@ -187,29 +262,25 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const bf16_t *__restri
 // Final conv C -> 64 output channels per grid.y slice, summed over the pixels of one (image, column
 // block).  partial[n][colblk*2 + xb][slice*64 + cb*32 + half*16 + v]
 template <int C, bool RELU>
-__global__ __launch_bounds__(256, 2) void conv_final_kernel(const bf16_t *__restrict__ in, ConvGeom g, int nbp,
+__global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
+                                                            ConvGeom g, int nbp,
                                                             const bf16_t *__restrict__ wfrag,
                                                             const float *__restrict__ bias,
                                                             float *__restrict__ partial)
 {
     typedef MidCfg<C> K;
     constexpr int RW = kRows;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[K::LDS_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[K::LDS_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int px = lane & 31, half = lane >> 5;
     const int cb = wave & 1, xb = wave >> 1;
     const int slice = blockIdx.y;
     const int cout0 = slice * 64 + cb * 32; // first output channel of this wavefront
 
     bf16x8 Wr[9][K::KC];
-    {
-        const bf16x8 *wp = (const bf16x8 *)wfrag + (int64_t)(cout0 / 32) * 9 * K::KC * 64 + lane;
-#pragma unroll
-        for (int tap = 0; tap < 9; ++tap)
-#pragma unroll
-            for (int kc = 0; kc < K::KC; ++kc) Wr[tap][kc] = wp[(tap * K::KC + kc) * 64];
-    }
+    load_weight_frags<C>(Wr, wfrag, cout0 / 32, lane);
     float bias16[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) bias16[v] = (RELU && bias) ? bias[cout0 + half * 16 + v] : 0.f;
@@ -220,86 +291,63 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const bf16_t *__rest
     const int per = (total + nb - 1) / nb;
     const int t_begin = vb * per;
     const int t_end = min(total, t_begin + per);
+    const uint8_t *lbase = lds + (xb * 32 + px) * K::PS + half * 16;
+    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
 
     for (int t = t_begin; t < t_end; ++t) {
         const int colblk = t % g.colblks;
         const int n = t / g.colblks;
         const int x0 = colblk * kTileW;
-        const int64_t img_base = (int64_t)n * g.h * g.w;
         const int x = x0 + xb * 32 + px;
 
-        f32x16 sum0, sum1;
+        f32x16 sum[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { sum0[v] = 0.f; sum1[v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { sum[0][v] = 0.f; sum[1][v] = 0.f; }
 
+        __syncthreads();
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, wave, lane);
         for (int strip = 0; strip < g.strips; ++strip) {
             const int y0 = strip * kRows;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            stage_strip<C>(lds, in, img_base, g.h, g.w, y0, x0, tid);
-            __syncthreads();
-
-            const uint8_t *lbase = lds + (xb * 32 + px) * K::PS + half * 16;
             if (!RELU) {
-                // rows share accumulators: the pixel sum is linear
-#pragma unroll
-                for (int r = 0; r < RW + 2; ++r) {
-#pragma unroll
-                    for (int dx = 0; dx < 3; ++dx) {
-#pragma unroll
-                        for (int kc = 0; kc < K::KC; ++kc) {
-                            const bf16x8 b = *(const bf16x8 *)(lbase + (r * kHaloW + dx) * K::PS + kc * 32);
-#pragma unroll
-                            for (int dy = 0; dy < 3; ++dy) {
-                                const int orow = r - dy;
-                                if (orow >= 0 && orow < RW && y0 + orow < g.h) {
-                                    if (orow & 1) sum1 = mfma32(Wr[dy * 3 + dx][kc], b, sum1);
-                                    else sum0 = mfma32(Wr[dy * 3 + dx][kc], b, sum0);
-                                }
-                            }
-                        }
-                    }
-                }
+                if (g.h - y0 >= RW) strip_mma<C, RW, true, false>(lbase, Wr, sum, RW);
+                else strip_mma<C, RW, true, true>(lbase, Wr, sum, g.h - y0);
+                __syncthreads();
+                if (strip + 1 < g.strips)
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave,
+                                         lane);
             } else {
                 f32x16 acc[RW];
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[r][v] = 0.f;
-#pragma unroll
-                for (int r = 0; r < RW + 2; ++r) {
-#pragma unroll
-                    for (int dx = 0; dx < 3; ++dx) {
-#pragma unroll
-                        for (int kc = 0; kc < K::KC; ++kc) {
-                            const bf16x8 b = *(const bf16x8 *)(lbase + (r * kHaloW + dx) * K::PS + kc * 32);
-#pragma unroll
-                            for (int dy = 0; dy < 3; ++dy) {
-                                const int orow = r - dy;
-                                if (orow >= 0 && orow < RW) acc[orow] = mfma32(Wr[dy * 3 + dx][kc], b, acc[orow]);
-                            }
-                        }
-                    }
-                }
+                    for (int v = 0; v < 16; ++v) acc[r][v] = bias16[v];
+                strip_mma<C, RW, false>(lbase, Wr, acc, RW);
+                __syncthreads();
+                if (strip + 1 < g.strips)
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave,
+                                         lane);
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
                     if (y0 + r < g.h)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) sum0[v] += fmaxf(acc[r][v] + bias16[v], 0.f);
+                        for (int v = 0; v < 16; ++v) sum[0][v] += fmaxf(acc[r][v], 0.f);
             }
         }
 
         // mask columns beyond the tile, reduce over the 32 pixel lanes of each half
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float s = (x < g.w) ? (sum0[v] + sum1[v]) : 0.f;
+            float s = (x < g.w) ? (sum[0][v] + sum[1][v]) : 0.f;
 #pragma unroll
             for (int off = 16; off >= 1; off >>= 1) s += __shfl_xor(s, off, 32);
-            sum0[v] = s;
+            sum[0][v] = s;
         }
         if (px == 0) {
             float *dst = partial + ((int64_t)n * (g.colblks * 2) + colblk * 2 + xb) * nbp + cout0 + half * 16;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dst[v] = sum0[v];
+            for (int v = 0; v < 16; ++v) dst[v] = sum[0][v];
         }
     }
 }
@@ -367,19 +415,18 @@ __global__ __launch_bounds__(256) void conv_first_kernel(TileSrc src, ConvGeom g
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             f32x16 acc;
+            {
+                const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+                for (int q = 0; q < 4; ++q) {
+                    const float4 bq = bp[q];
+                    acc[4 * q] = bq.x; acc[4 * q + 1] = bq.y; acc[4 * q + 2] = bq.z; acc[4 * q + 3] = bq.w;
+                }
+            }
             acc = mfma32(Wr[cb][0], bfrag[0], acc);
             acc = mfma32(Wr[cb][1], bfrag[1], acc);
-            float bias16[16];
-            const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 bq = bp[q];
-                bias16[4 * q] = bq.x; bias16[4 * q + 1] = bq.y; bias16[4 * q + 2] = bq.z; bias16[4 * q + 3] = bq.w;
-            }
             if (x < g.w)
-                store_tile_bf16(out + ((n * g.h + y) * (int64_t)g.w + x) * C + cb * 32 + half * 16, acc, bias16, true);
+                store_tile_bf16(out + ((n * g.h + y) * (int64_t)g.w + x) * C + cb * 32 + half * 16, acc, true);
         }
     }
 }
@@ -454,31 +501,32 @@ hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const
     return hipGetLastError();
 }
 
-hipError_t launch_conv_mid(const bf16_t *in, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
-                           bf16_t *out, int num_cu, hipStream_t s)
+hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
+                           const float *bias, bf16_t *out, int num_cu, hipStream_t s)
 {
     const int64_t tiles = (int64_t)g.n_img * g.strips * g.colblks;
     const int blocks = persistent_blocks(num_cu, 2, tiles);
     if (C == 64)
-        hipLaunchKernelGGL(conv_mid_kernel<64>, dim3(blocks), dim3(256), 0, s, in, g, wfrag, bias, out);
+        hipLaunchKernelGGL(conv_mid_kernel<64>, dim3(blocks), dim3(256), 0, s, ws, in_off, g, wfrag, bias, out);
     else
-        hipLaunchKernelGGL(conv_mid_kernel<32>, dim3(blocks), dim3(256), 0, s, in, g, wfrag, bias, out);
+        hipLaunchKernelGGL(conv_mid_kernel<32>, dim3(blocks), dim3(256), 0, s, ws, in_off, g, wfrag, bias, out);
     return hipGetLastError();
 }
 
-hipError_t launch_conv_final(const bf16_t *in, const ConvGeom &g, int C, int nbp, const bf16_t *wfrag,
-                             const float *bias, int relu, float *partial, int num_cu, hipStream_t s)
+hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
+                             const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,
+                             hipStream_t s)
 {
     const int64_t units = (int64_t)g.n_img * g.colblks;
     const int slices = nbp / 64;
     int blocks = persistent_blocks(num_cu, 2, units);
     dim3 grid(blocks, slices);
     if (C == 64) {
-        if (relu) hipLaunchKernelGGL((conv_final_kernel<64, true>), grid, dim3(256), 0, s, in, g, nbp, wfrag, bias, partial);
-        else hipLaunchKernelGGL((conv_final_kernel<64, false>), grid, dim3(256), 0, s, in, g, nbp, wfrag, bias, partial);
+        if (relu) hipLaunchKernelGGL((conv_final_kernel<64, true>), grid, dim3(256), 0, s, ws, in_off, g, nbp, wfrag, bias, partial);
+        else hipLaunchKernelGGL((conv_final_kernel<64, false>), grid, dim3(256), 0, s, ws, in_off, g, nbp, wfrag, bias, partial);
     } else {
-        if (relu) hipLaunchKernelGGL((conv_final_kernel<32, true>), grid, dim3(256), 0, s, in, g, nbp, wfrag, bias, partial);
-        else hipLaunchKernelGGL((conv_final_kernel<32, false>), grid, dim3(256), 0, s, in, g, nbp, wfrag, bias, partial);
+        if (relu) hipLaunchKernelGGL((conv_final_kernel<32, true>), grid, dim3(256), 0, s, ws, in_off, g, nbp, wfrag, bias, partial);
+        else hipLaunchKernelGGL((conv_final_kernel<32, false>), grid, dim3(256), 0, s, ws, in_off, g, nbp, wfrag, bias, partial);
     }
     return hipGetLastError();
 }

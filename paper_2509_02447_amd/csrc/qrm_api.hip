@@ -132,6 +132,10 @@ int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w)
 {
     int mb = c->micro_batch > 0 ? c->micro_batch : default_micro_batch(c, h, w);
     if ((int64_t)mb > N) mb = (int)(N > 0 ? N : 1);
+    // the kernels address both activation buffers with 32-bit byte offsets from the workspace base
+    const size_t per_img = (size_t)h * w * c->C * 2;
+    const size_t cap = ((size_t)1900 << 20) / (per_img ? per_img : 1);
+    if ((size_t)mb > cap) mb = (int)(cap > 0 ? cap : 1);
     return mb;
 }
 
@@ -150,7 +154,7 @@ WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
         L.partial = align_up((size_t)L.mb * L.n_part * c->nbp * 4);
     }
     L.symbols = (want_symbols && c->has_rs) ? align_up((size_t)N * c->rs.n) : 0;
-    L.total = 2 * L.act + L.partial + L.symbols;
+    L.total = kZeroBytes + 2 * L.act + L.partial + L.symbols;
     return L;
 }
 
@@ -179,6 +183,9 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
             return fail(c, QRM_E_NOMEM, buf);
         }
         slot->bytes = bytes;
+        // the block of zeros the convolutions read their padding from; written once per allocation
+        e = hipMemset(slot->ws, 0, kZeroBytes);
+        if (e != hipSuccess) return hip_fail(c, e, "hipMemset(workspace zero block)");
     }
     *out = slot;
     return QRM_OK;
@@ -190,8 +197,9 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
                          float *d_logits, uint8_t *d_bits, uint8_t *d_symbols, int m_sym, float *d_act, hipStream_t s)
 {
     uint8_t *base = (uint8_t *)slot->ws;
-    bf16_t *buf[2] = {(bf16_t *)base, (bf16_t *)(base + L.act)};
-    float *partial = (float *)(base + 2 * L.act);
+    const uint32_t buf_off[2] = {(uint32_t)kZeroBytes, (uint32_t)(kZeroBytes + L.act)};
+    bf16_t *buf[2] = {(bf16_t *)(base + buf_off[0]), (bf16_t *)(base + buf_off[1])};
+    float *partial = (float *)(base + kZeroBytes + 2 * L.act);
     const int nsym = (d_symbols && m_sym > 0) ? c->n_bits / m_sym : 0;
     const uint8_t *img0 = src.img;
     const int32_t *off0 = src.off;
@@ -221,8 +229,8 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
                 c->ev_used += 2;
                 (void)hipEventRecord(ev0, s);
             }
-            e = launch_conv_mid(buf[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C, buf[cur ^ 1],
-                                c->num_cu, s);
+            e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C,
+                                buf[cur ^ 1], c->num_cu, s);
             if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
             if (c->profile) {
                 (void)hipEventRecord(ev1, s);
@@ -235,8 +243,8 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
             if (e != hipSuccess) return hip_fail(c, e, "nhwc_to_nchw launch");
             continue;
         }
-        e = launch_conv_final(buf[cur], g, c->C, c->nbp, c->d_w_final, c->d_bias_final, c->final_relu, partial,
-                              c->num_cu, s);
+        e = launch_conv_final(base, buf_off[cur], g, c->C, c->nbp, c->d_w_final, c->d_bias_final, c->final_relu,
+                              partial, c->num_cu, s);
         if (e != hipSuccess) return hip_fail(c, e, "conv_final launch");
         e = launch_linear_pack(partial, L.n_part, c->nbp, cnt, c->n_bits, 1.0f / ((float)h * (float)w),
                                c->final_relu ? nullptr : c->d_bias_final, c->d_lin_w, c->d_lin_b,
@@ -521,7 +529,7 @@ qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H,
     Slot *slot = nullptr;
     qrm_status st = get_slot(c, s, L.total, &slot);
     if (st != QRM_OK) return st;
-    uint8_t *d_sym = (uint8_t *)slot->ws + 2 * L.act + L.partial;
+    uint8_t *d_sym = (uint8_t *)slot->ws + kZeroBytes + 2 * L.act + L.partial;
     TileSrc src{d_images, d_off_yx, H, W, {c->mean[0], c->mean[1], c->mean[2]},
                 {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
     st = run_extractor(c, slot, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, s);

@@ -45,14 +45,17 @@ hipError_t launch_extract_tiles(const uint8_t *img, int64_t N, int H, int W, con
 hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
                              bf16_t *out, int num_cu, hipStream_t s);
 
-// conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out
-hipError_t launch_conv_mid(const bf16_t *in, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
-                           bf16_t *out, int num_cu, hipStream_t s);
+// conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out.  The input is addressed as ws + in_off (+ 32-bit
+// offsets); the first kZeroBytes of ws must be zero: they are the source of the zero padding.
+constexpr size_t kZeroBytes = 256;
+hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
+                           const float *bias, bf16_t *out, int num_cu, hipStream_t s);
 
 // final conv3x3 C -> nbp (n_bits padded to 32s) (+bias, optional ReLU) + sum over pixels -> partial sums
 // partial: f32 [n_img][colblks*2][nbp]
-hipError_t launch_conv_final(const bf16_t *in, const ConvGeom &g, int C, int nbp, const bf16_t *wfrag,
-                             const float *bias, int relu, float *partial, int num_cu, hipStream_t s);
+hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
+                             const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,
+                             hipStream_t s);
 
 // pooled = sum(partials)/(h*w); logits = lin_w * pooled + lin_b; bits; symbols (MSB first, m bits each)
 // fbias: optional bias of the final convolution, added to the pooled value
