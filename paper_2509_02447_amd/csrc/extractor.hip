@@ -177,17 +177,72 @@ __device__ __forceinline__ void load_weight_frags(bf16x8 (&Wr)[9][C / 16], const
         for (int kc = 0; kc < K::KC; ++kc) Wr[tap][kc] = wp[(tap * K::KC + kc) * 64];
 }
 
+// ---- per-image channel statistics ---------------------------------------------------------------
+// Every layer hands the next one per-image channel sums of its (post-ReLU) output.  They serve two
+// purposes:
+//  (1) weights are bf16 on the matrix cores; the rounding residual W - bf16(W) acts on the mean
+//      activation as a constant per output channel, the only part of the rounding error that global
+//      average pooling does not wash out.  The consumer adds sum_c rsum[o][c] * mean[c] to its bias
+//      (rsum = residual summed over the 9 taps), with mean estimated from every fourth strip.
+//  (2) the last conv (C -> n_bits, no ReLU) followed by the global average pool is linear, so it only
+//      needs, per channel of the last block's output, the sums over the whole tile, its first / last
+//      row, first / last column and four corners (9 numbers): the last block writes no activations.
+// A record is written per (image, workgroup that touched it): rec[q*C + c] sums, rec[NQ*C] = pixel count.
+// Accumulation order is fixed, so results do not depend on scheduling.
+constexpr int kStatPad = 16;
+__host__ __device__ constexpr int stat_rec(int C, int nq) { return nq * C + kStatPad; }
+
+__device__ __forceinline__ float half_sum(float v) // over the 32 pixel lanes of one half-wavefront
+{
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 32);
+    return v;
+}
+
+// lanes with `pred` add their 16 values into this wavefront's private LDS accumulators
+__device__ __forceinline__ void lds_accumulate(float *slot16, const float (&tv)[16], bool pred)
+{
+    if (pred) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            f32x4 cur = *(f32x4 *)(slot16 + 4 * q);
+            cur[0] += tv[4 * q]; cur[1] += tv[4 * q + 1]; cur[2] += tv[4 * q + 2]; cur[3] += tv[4 * q + 3];
+            *(f32x4 *)(slot16 + 4 * q) = cur;
+        }
+    }
+}
+
+struct StatArgs {
+    const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
+    int in_slots;
+    const float *rsum;  // [C][C] residual-weight sums of this layer (fp32), or nullptr
+    float *tout;        // records written by this launch [n_img][out_slots][stat_rec(C,NQ)], or nullptr
+    int out_slots;
+    int per;            // tiles per workgroup: divides, or is a multiple of, the tiles of one image
+};
+
+constexpr int MODE_MID = 0;  // write activations, sample channel sums from every fourth strip
+constexpr int MODE_LAST = 1; // last block: no activations, the nine border-aware channel sums
+
 // C -> C (+bias, ReLU), bf16 NHWC in / out.  Two workgroups per CU: while one waits for its strip to
 // land in LDS the other keeps the matrix cores busy.
-template <int C>
+template <int C, int MODE>
 __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
                                                           ConvGeom g, const bf16_t *__restrict__ wfrag,
-                                                          const float *__restrict__ bias, bf16_t *__restrict__ out)
+                                                          const float *__restrict__ bias, StatArgs st,
+                                                          bf16_t *__restrict__ out)
 {
     typedef MidCfg<C> K;
     constexpr int RG = 2 / K::NCB;     // row groups among the 4 wavefronts
     constexpr int RW = kRows / RG;     // output rows per wavefront
+    constexpr int NQ = MODE == MODE_LAST ? 9 : 1;
+    constexpr int PARTS = 256 / C;
     __shared__ __attribute__((aligned(1024))) uint8_t lds[K::LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) float s_stat[4][NQ][32]; // per wavefront, 32 channels of its block
+    __shared__ __attribute__((aligned(16))) float s_init[C];         // bias + rounding-residual correction
+    __shared__ float s_mean[C];
+    __shared__ float s_red[PARTS][C];
+    __shared__ float s_cnt[4];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -198,42 +253,102 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
 
     bf16x8 Wr[9][K::KC];
     load_weight_frags<C>(Wr, wfrag, cb, lane);
-    const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
 
-    const int total = g.n_img * g.strips * g.colblks;
-    const int nb = gridDim.x;
-    const int vb = xcd_virtual_block(blockIdx.x, nb);
-    const int per = (total + nb - 1) / nb;
-    const int t_begin = vb * per;
-    const int t_end = min(total, t_begin + per);
+    const int tpi = g.strips * g.colblks; // tiles per image
+    const int total = g.n_img * tpi;
+    const int vb = xcd_virtual_block(blockIdx.x, gridDim.x);
+    const int t_begin = vb * st.per;
+    const int t_end = min(total, t_begin + st.per);
+    const int out_slot = st.per >= tpi ? 0 : (t_begin % tpi) / st.per;
     const uint8_t *lbase = lds + (rg * RW) * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
+    float *my_stat = &s_stat[wave][0][half * 16];
 
-    auto decode = [&](int t, int &n, int &y0, int &x0) {
+    auto decode = [&](int t, int &n, int &strip, int &x0) {
         const int colblk = t % g.colblks;
-        const int strip = (t / g.colblks) % g.strips;
-        n = t / (g.colblks * g.strips);
-        y0 = strip * kRows;
+        strip = (t / g.colblks) % g.strips;
+        n = t / tpi;
         x0 = colblk * kTileW;
     };
+    auto zero_stats = [&]() {
+        for (int i = tid; i < 4 * NQ * 32; i += 256) (&s_stat[0][0][0])[i] = 0.f;
+        if (tid < 4) s_cnt[tid] = 0.f;
+    };
+    // writes the record of image n and clears the accumulators
+    auto flush = [&](int n) {
+        __syncthreads();
+        float *rec = st.tout + ((int64_t)n * st.out_slots + out_slot) * stat_rec(C, NQ);
+        for (int i = tid; i < NQ * C; i += 256) {
+            const int q = i / C, o = i - q * C;
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                if (w % K::NCB == o / 32) v += s_stat[w][q][o & 31];
+            rec[i] = v;
+        }
+        if (tid == 0) rec[NQ * C] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        __syncthreads();
+        zero_stats();
+        __syncthreads();
+    };
+    // s_init[o] = bias[o] + sum_c rsum[o][c] * mean_n[c]
+    auto prepare_init = [&](int n) {
+        __syncthreads();
+        if (st.tin && st.rsum) {
+            if (tid < C) {
+                float sum = 0.f, cnt = 0.f;
+                for (int s2 = 0; s2 < st.in_slots; ++s2) {
+                    const float *rec = st.tin + ((int64_t)n * st.in_slots + s2) * stat_rec(C, 1);
+                    sum += rec[tid];
+                    cnt += rec[C];
+                }
+                s_mean[tid] = cnt > 0.f ? sum / cnt : 0.f;
+            }
+            __syncthreads();
+            {
+                const int o = tid % C, part = tid / C;
+                float d = 0.f;
+                for (int c = part * (C / PARTS); c < (part + 1) * (C / PARTS); ++c) d = fmaf(st.rsum[o * C + c], s_mean[c], d);
+                s_red[part][o] = d;
+            }
+            __syncthreads();
+            if (tid < C) {
+                float v = bias[tid];
+#pragma unroll
+                for (int p2 = 0; p2 < PARTS; ++p2) v += s_red[p2][tid];
+                s_init[tid] = v;
+            }
+        } else if (tid < C) {
+            s_init[tid] = bias[tid];
+        }
+        __syncthreads();
+    };
 
+    zero_stats();
     if (t_begin < t_end) {
-        int n, y0, x0;
-        decode(t_begin, n, y0, x0);
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, y0, x0, wave,
-                             lane);
+        int n, strip, x0;
+        decode(t_begin, n, strip, x0);
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, strip * kRows, x0,
+                             wave, lane);
     }
+    int cur_n = -1;
     for (int t = t_begin; t < t_end; ++t) {
-        int n, y0, x0;
-        decode(t, n, y0, x0);
+        int n, strip, x0;
+        decode(t, n, strip, x0);
+        const int y0 = strip * kRows;
+        if (n != cur_n) { // same for the whole workgroup
+            if (cur_n >= 0 && st.tout) flush(cur_n);
+            prepare_init(n);
+            cur_n = n;
+        }
 
-        // accumulators start from the bias (16 consecutive channels per lane)
+        // accumulators start from bias + correction (16 consecutive channels per lane)
         f32x16 acc[RW];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 bq = bp[q];
+            const f32x4 bq = *(const f32x4 *)(&s_init[cb * 32 + half * 16 + 4 * q]);
 #pragma unroll
             for (int r = 0; r < RW; ++r) {
-                acc[r][4 * q] = bq.x; acc[r][4 * q + 1] = bq.y; acc[r][4 * q + 2] = bq.z; acc[r][4 * q + 3] = bq.w;
+                acc[r][4 * q] = bq[0]; acc[r][4 * q + 1] = bq[1]; acc[r][4 * q + 2] = bq[2]; acc[r][4 * q + 3] = bq[3];
             }
         }
 
@@ -242,21 +357,80 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
         strip_mma<C, RW, false>(lbase, Wr, acc, RW);
         __syncthreads(); // everyone is done reading: the buffer may be refilled
         if (t + 1 < t_end) {
-            int n2, y2, x2;
-            decode(t + 1, n2, y2, x2);
-            issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n2 * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, y2, x2,
-                                 wave, lane);
+            int n2, strip2, x2;
+            decode(t + 1, n2, strip2, x2);
+            issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n2 * (uint32_t)(g.h * g.w * C * 2), g.h, g.w,
+                                 strip2 * kRows, x2, wave, lane);
         }
 
         const int x = x0 + xb * 32 + px;
-        const int64_t img_base = (int64_t)n * g.h * g.w;
+        const int yw = y0 + rg * RW; // first output row of this wavefront
+        if (MODE == MODE_MID) {
+            const int64_t img_base = (int64_t)n * g.h * g.w;
 #pragma unroll
-        for (int r = 0; r < RW; ++r) {
-            const int y = y0 + rg * RW + r;
-            if (y < g.h && x < g.w)
-                store_tile_bf16(out + (img_base + (int64_t)y * g.w + x) * C + cb * 32 + half * 16, acc[r], true);
+            for (int r = 0; r < RW; ++r) {
+                const int y = yw + r;
+                if (y < g.h && x < g.w)
+                    store_tile_bf16(out + (img_base + (int64_t)y * g.w + x) * C + cb * 32 + half * 16, acc[r], true);
+            }
+        }
+        if (st.tout && (MODE == MODE_LAST || (strip & 3) == 0)) {
+            // per-lane sum over this wavefront's valid rows of relu(output)
+            float tv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tv[v] = 0.f;
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+                if (yw + r < g.h) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) tv[v] += fmaxf(acc[r][v], 0.f);
+                }
+            if (x >= g.w) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) tv[v] = 0.f;
+            }
+            if (MODE == MODE_LAST) {
+                lds_accumulate(my_stat + 3 * 32, tv, x == 0);         // first column
+                lds_accumulate(my_stat + 4 * 32, tv, x == g.w - 1);   // last column
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tv[v] = half_sum(tv[v]);
+            lds_accumulate(my_stat, tv, px == 0);                    // whole tile (or its sampled strips)
+            if (cb == 0 && lane == 0) {
+                const int rows = max(0, min(RW, g.h - yw)), cols = max(0, min(32, g.w - (x0 + xb * 32)));
+                s_cnt[wave] += (float)(rows * cols);
+            }
+            if (MODE == MODE_LAST) {
+                if (yw == 0) { // image row 0 is this wavefront's first row
+                    float rv[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) rv[v] = x < g.w ? fmaxf(acc[0][v], 0.f) : 0.f;
+                    lds_accumulate(my_stat + 5 * 32, rv, x == 0);
+                    lds_accumulate(my_stat + 6 * 32, rv, x == g.w - 1);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
+                    lds_accumulate(my_stat + 1 * 32, rv, px == 0);
+                }
+                const int rl = g.h - 1 - yw; // image row h-1 relative to this wavefront's rows
+                if (rl >= 0 && rl < RW) {
+                    float rv[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float a = acc[0][v];
+#pragma unroll
+                        for (int r = 1; r < RW; ++r) a = rl == r ? acc[r][v] : a;
+                        rv[v] = x < g.w ? fmaxf(a, 0.f) : 0.f;
+                    }
+                    lds_accumulate(my_stat + 7 * 32, rv, x == 0);
+                    lds_accumulate(my_stat + 8 * 32, rv, x == g.w - 1);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
+                    lds_accumulate(my_stat + 2 * 32, rv, px == 0);
+                }
+            }
         }
     }
+    if (cur_n >= 0 && st.tout) flush(cur_n);
 }
 
 // Final conv C -> 64 output channels per grid.y slice, summed over the pixels of one (image, column
@@ -354,79 +528,266 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
 
 // ------------------------------------------------------------------------------------------------
 // First layer: u8 planes -> crop -> normalise -> conv3x3 (3 -> C) + bias + ReLU -> bf16 NHWC.
-// One wavefront per (image, row, 32-column block); K = 27 (tap-major, channel-minor) padded to 32.
+// A workgroup stages the (4+2) x (64+2) window of the tile as normalised bf16 pixels of 4 channels
+// (r, g, b, 0 = 8 bytes) in LDS; whatever lies outside the tile is a literal zero, i.e. zero padding in
+// the normalised domain.  K = 9 taps x 4 channels = 36, padded to 48 = three 16-wide k chunks; a lane's
+// 8 k values of a chunk are two taps, i.e. two 8-byte LDS reads.  A wavefront computes one 32-channel
+// output block for one (C = 32) or two (C = 64) rows of the strip.
 // ------------------------------------------------------------------------------------------------
+constexpr int kFirstPix = (kRows + 2) * kHaloW;
+
 template <int C>
-__global__ __launch_bounds__(256) void conv_first_kernel(TileSrc src, ConvGeom g, const bf16_t *__restrict__ wfrag,
-                                                         const float *__restrict__ bias, bf16_t *__restrict__ out)
+__global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeom g, const bf16_t *__restrict__ wfrag,
+                                                         const float *__restrict__ bias, float *__restrict__ tout,
+                                                         int out_slots, int per, bf16_t *__restrict__ out)
 {
     constexpr int NCB = C / 32;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[kFirstPix * 4];
+    __shared__ __attribute__((aligned(16))) float s_stat[4][32]; // per wavefront, the 32 channels of its block
+    __shared__ float s_cnt[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int px = lane & 31, half = lane >> 5;
 
-    bf16x8 Wr[NCB][2];
+    // a wavefront owns one 32-channel output block and NCB of the strip's rows
+    const int cb = wave % NCB;
+    const int rbase = (wave / NCB) * NCB;
+    // weights as bf16 high part + bf16 residual: this layer is tiny, so it is computed to ~16 bits
+    bf16x8 Wr[2][3];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
+    for (int p = 0; p < 2; ++p)
 #pragma unroll
-        for (int kc = 0; kc < 2; ++kc) Wr[cb][kc] = ((const bf16x8 *)wfrag)[(cb * 2 + kc) * 64 + lane];
-
-    // per-lane description of its 16 k indices: k = kc*16 + half*8 + e  ->  (tap, channel)
-    int koff[16];      // byte offset relative to the centre pixel of plane 0
-    int kdy[16], kdx[16];
-    float ka[16], kb[16]; // normalised = byte * ka + kb
-    const int plane = src.H * src.W;
+        for (int q = 0; q < 3; ++q) Wr[p][q] = ((const bf16x8 *)wfrag)[((cb * 2 + p) * 3 + q) * 64 + lane];
+    f32x16 bias16;
+    {
+        const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int kk = (i >> 3) * 16 + half * 8 + (i & 7);
-        const bool kvalid = kk < 27;
-        const int tap = kvalid ? kk / 3 : 0, c = kvalid ? kk % 3 : 0;
-        kdy[i] = kvalid ? tap / 3 - 1 : 1 << 20; // an invalid k never passes the bounds test
-        kdx[i] = tap % 3 - 1;
-        koff[i] = c * plane + (tap / 3 - 1) * src.W + (tap % 3 - 1);
-        const float istd = c == 0 ? src.inv_std[0] : (c == 1 ? src.inv_std[1] : src.inv_std[2]);
-        const float mean = c == 0 ? src.mean[0] : (c == 1 ? src.mean[1] : src.mean[2]);
-        ka[i] = istd * (1.0f / 255.0f);
-        kb[i] = -mean * istd;
+        for (int q = 0; q < 4; ++q) {
+            const float4 bq = bp[q];
+            bias16[4 * q] = bq.x; bias16[4 * q + 1] = bq.y; bias16[4 * q + 2] = bq.z; bias16[4 * q + 3] = bq.w;
+        }
     }
 
-    const int cblk32 = (g.w + 31) / 32;
-    const int64_t total = (int64_t)g.n_img * g.h * cblk32;
-    const int64_t wstride = (int64_t)gridDim.x * 4;
-    for (int64_t item = (int64_t)blockIdx.x * 4 + wave; item < total; item += wstride) {
-        const int xc = (int)(item % cblk32);
-        const int y = (int)((item / cblk32) % g.h);
-        const int64_t n = item / ((int64_t)cblk32 * g.h);
+    // LDS byte offsets (relative to the lane's output pixel) of the two taps of each k chunk:
+    // chunk q, half h -> taps 4q + 2h and 4q + 2h + 1; taps >= 9 carry zero weights and re-read tap 8.
+    int toff[3][2];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            int tap = 4 * q + 2 * half + j;
+            tap = tap > 8 ? 8 : tap;
+            toff[q][j] = ((tap / 3) * kHaloW + tap % 3) * 8;
+        }
+    for (int i = tid; i < kFirstPix; i += 256) lds[i * 4 + 3] = 0; // the padding channel stays zero
+    for (int i = tid; i < 4 * 32; i += 256) (&s_stat[0][0])[i] = 0.f;
+    if (tid < 4) s_cnt[tid] = 0.f;
+
+    const int plane = src.H * src.W;
+    const float ka[3] = {src.inv_std[0] * (1.0f / 255.0f), src.inv_std[1] * (1.0f / 255.0f),
+                         src.inv_std[2] * (1.0f / 255.0f)};
+    const float kb[3] = {-src.mean[0] * src.inv_std[0], -src.mean[1] * src.inv_std[1], -src.mean[2] * src.inv_std[2]};
+
+    const int tpi = g.strips * g.colblks;
+    const int total = g.n_img * tpi;
+    const int t_begin = blockIdx.x * per;
+    const int t_end = min(total, t_begin + per);
+    const int out_slot = per >= tpi ? 0 : (t_begin % tpi) / per;
+
+    auto flush = [&](int n) {
+        __syncthreads();
+        float *rec = tout + ((int64_t)n * out_slots + out_slot) * stat_rec(C, 1);
+        if (tid < C) {
+            float v = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2)
+                if (w2 % NCB == tid / 32) v += s_stat[w2][tid & 31];
+            rec[tid] = v;
+        }
+        if (tid == 0) rec[C] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        __syncthreads();
+        for (int i = tid; i < 4 * 32; i += 256) (&s_stat[0][0])[i] = 0.f;
+        if (tid < 4) s_cnt[tid] = 0.f;
+        __syncthreads();
+    };
+
+    int cur_n = -1;
+    for (int t = t_begin; t < t_end; ++t) {
+        const int colblk = t % g.colblks;
+        const int strip = (t / g.colblks) % g.strips;
+        const int n = t / tpi;
+        const int y0 = strip * kRows, x0 = colblk * kTileW;
+        if (n != cur_n) {
+            if (cur_n >= 0 && tout) flush(cur_n);
+            cur_n = n;
+        }
         int oy = 0, ox = 0;
         if (src.off) {
             oy = clampi(src.off[2 * n], 0, src.H - g.h);
             ox = clampi(src.off[2 * n + 1], 0, src.W - g.w);
         }
-        const int x = xc * 32 + px;
-        const uint8_t *centre = src.img + n * 3 * (int64_t)plane + (int64_t)(oy + y) * src.W + ox + x;
+        const uint8_t *tile0 = src.img + (int64_t)n * 3 * plane + (int64_t)oy * src.W + ox;
 
-        bf16x8 bfrag[2];
+        __syncthreads(); // previous strip fully consumed
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int ty = y + kdy[i], tx = x + kdx[i];
-            float val = 0.f;
-            if (ty >= 0 && ty < g.h && tx >= 0 && tx < g.w) val = fmaf((float)centre[koff[i]], ka[i], kb[i]);
-            bfrag[i >> 3][i & 7] = (bf16_t)val;
+        for (int it = 0; it < (kFirstPix * 3 + 255) / 256; ++it) {
+            const int idx = tid + it * 256;
+            if (idx < kFirstPix * 3) {
+                const int c = idx / kFirstPix, p = idx - c * kFirstPix;
+                const int row = p / kHaloW, col = p - row * kHaloW;
+                const int ty = y0 - 1 + row, tx = x0 - 1 + col;
+                float v = 0.f;
+                if (ty >= 0 && ty < g.h && tx >= 0 && tx < g.w) {
+                    const float a = c == 0 ? ka[0] : (c == 1 ? ka[1] : ka[2]);
+                    const float b = c == 0 ? kb[0] : (c == 1 ? kb[1] : kb[2]);
+                    v = fmaf((float)tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx], a, b);
+                }
+                lds[p * 4 + c] = __builtin_bit_cast(uint16_t, (bf16_t)v);
+            }
         }
+        __syncthreads();
+
+        const bool sample = tout && (strip & 3) == 0;
 #pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) {
-            f32x16 acc;
-            {
-                const float4 *bp = (const float4 *)(bias + cb * 32 + half * 16);
+        for (int rr = 0; rr < NCB; ++rr) {
+            const int row = rbase + rr;
+            const int y = y0 + row;
+            if (y >= g.h) continue; // same for the whole wavefront
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 bq = bp[q];
-                    acc[4 * q] = bq.x; acc[4 * q + 1] = bq.y; acc[4 * q + 2] = bq.z; acc[4 * q + 3] = bq.w;
+            for (int xb = 0; xb < 2; ++xb) {
+                const int x = x0 + xb * 32 + px;
+                const uint8_t *lp = (const uint8_t *)lds + (row * kHaloW + xb * 32 + px) * 8;
+                bf16x8 bfrag[3];
+#pragma unroll
+                for (int q = 0; q < 3; ++q) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 lo = *(const u32x2 *)(lp + toff[q][0]);
+                    const u32x2 hi = *(const u32x2 *)(lp + toff[q][1]);
+                    const u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+                    bfrag[q] = __builtin_bit_cast(bf16x8, both);
+                }
+                f32x16 acc = bias16;
+#pragma unroll
+                for (int p = 0; p < 2; ++p)
+#pragma unroll
+                    for (int q = 0; q < 3; ++q) acc = mfma32(Wr[p][q], bfrag[q], acc);
+                if (x < g.w)
+                    store_tile_bf16(out + (((int64_t)n * g.h + y) * g.w + x) * C + cb * 32 + half * 16, acc, true);
+                if (sample) {
+                    float tv[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) tv[v] = half_sum(x < g.w ? fmaxf(acc[v], 0.f) : 0.f);
+                    lds_accumulate(&s_stat[wave][half * 16], tv, px == 0);
+                    if (cb == 0 && lane == 0) s_cnt[wave] += (float)max(0, min(32, g.w - (x0 + xb * 32)));
                 }
             }
-            acc = mfma32(Wr[cb][0], bfrag[0], acc);
-            acc = mfma32(Wr[cb][1], bfrag[1], acc);
-            if (x < g.w)
-                store_tile_bf16(out + ((n * g.h + y) * (int64_t)g.w + x) * C + cb * 32 + half * 16, acc, true);
+        }
+    }
+    if (cur_n >= 0 && tout) flush(cur_n);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Head for the linear tail: the nine border-aware channel sums of the last block -> final conv + global
+// average pool in closed form (fp32 weights) -> linear -> logits -> bits -> symbols.
+//   pooled[o] = 1/(h w) * sum_{c,dy,dx} Wf[o][c][dy][dx] * S[c][dy][dx],
+//   S[c][dy][dx] = sum of channel c over the input pixels that tap (dy,dx) reaches with zero padding
+//                = whole - excluded row - excluded column + their corner
+//   (dy = 0 never reaches the last row, dy = 2 never the first; same for dx and columns).
+// IPB images per block share every weight read.
+// ------------------------------------------------------------------------------------------------
+constexpr int kHeadIpb = 2;   // images per block
+constexpr int kHeadKParts = 4; // the k = (channel, tap) range is cut in four, one part per 64 threads
+
+__global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ recs, int slots, int C, int n_img,
+                                                   int n_bits, int nbp, float inv_hw,
+                                                   const float *__restrict__ wft /*[C*9][nbp]*/,
+                                                   const float *__restrict__ fbias, const float *__restrict__ lin_w,
+                                                   const float *__restrict__ lin_b, float *__restrict__ logits,
+                                                   uint8_t *__restrict__ bits, uint8_t *__restrict__ symbols, int m)
+{
+    __shared__ float Q[kHeadIpb][9][64];
+    __shared__ float S[kHeadIpb][9 * 64]; // [c*9 + tap]
+    __shared__ float part[kHeadKParts][kHeadIpb][128];
+    __shared__ float pooled[kHeadIpb][128];
+    __shared__ uint8_t sbit[kHeadIpb][128];
+    const int tid = threadIdx.x;
+    const int64_t n0 = (int64_t)blockIdx.x * kHeadIpb;
+    const int rec = stat_rec(C, 9);
+    for (int idx = tid; idx < kHeadIpb * 9 * C; idx += 256) {
+        const int i = idx / (9 * C), r = idx - i * 9 * C; // r = q*C + c
+        float v = 0.f;
+        if (n0 + i < n_img)
+            for (int s2 = 0; s2 < slots; ++s2) v += recs[((n0 + i) * slots + s2) * rec + r];
+        Q[i][r / C][r % C] = v;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kHeadIpb * C; idx += 256) {
+        const int i = idx / C, c = idx - i * C;
+        const float T = Q[i][0][c], R0 = Q[i][1][c], Rl = Q[i][2][c], C0 = Q[i][3][c], Cl = Q[i][4][c];
+        const float c00 = Q[i][5][c], c0l = Q[i][6][c], cl0 = Q[i][7][c], cll = Q[i][8][c];
+#pragma unroll
+        for (int dy = 0; dy < 3; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < 3; ++dx) {
+                const float rex = dy == 0 ? Rl : (dy == 2 ? R0 : 0.f);
+                const float cex = dx == 0 ? Cl : (dx == 2 ? C0 : 0.f);
+                float corner = 0.f;
+                if (dy == 0 && dx == 0) corner = cll;
+                if (dy == 0 && dx == 2) corner = cl0;
+                if (dy == 2 && dx == 0) corner = c0l;
+                if (dy == 2 && dx == 2) corner = c00;
+                S[i][c * 9 + dy * 3 + dx] = T - rex - cex + corner;
+            }
+    }
+    __syncthreads();
+    // final conv + pool: thread (kp, ol) sums its quarter of k for outputs ol, ol + 64
+    {
+        const int kp = tid >> 6, ol = tid & 63;
+        const int klen = (C * 9) / kHeadKParts, k0 = kp * klen;
+        for (int o = ol; o < nbp; o += 64) {
+            float acc[kHeadIpb];
+#pragma unroll
+            for (int i = 0; i < kHeadIpb; ++i) acc[i] = 0.f;
+#pragma unroll 8
+            for (int k = k0; k < k0 + klen; ++k) {
+                const float wv = wft[(int64_t)k * nbp + o];
+#pragma unroll
+                for (int i = 0; i < kHeadIpb; ++i) acc[i] = fmaf(wv, S[i][k], acc[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < kHeadIpb; ++i) part[kp][i][o] = acc[i];
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kHeadIpb * n_bits; idx += 256) {
+        const int i = idx / n_bits, o = idx - i * n_bits;
+        float v = 0.f;
+#pragma unroll
+        for (int kp = 0; kp < kHeadKParts; ++kp) v += part[kp][i][o];
+        pooled[i][o] = v * inv_hw + (fbias ? fbias[o] : 0.f);
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kHeadIpb * n_bits; idx += 256) {
+        const int i = idx / n_bits, o = idx - i * n_bits;
+        float z = lin_b ? lin_b[o] : 0.f;
+        for (int k = 0; k < n_bits; ++k) z = fmaf(lin_w[o * n_bits + k], pooled[i][k], z);
+        const uint8_t bt = z > 0.f ? 1 : 0;
+        sbit[i][o] = bt;
+        if (n0 + i < n_img) {
+            if (logits) logits[(n0 + i) * n_bits + o] = z;
+            if (bits) bits[(n0 + i) * n_bits + o] = bt;
+        }
+    }
+    __syncthreads();
+    if (symbols) {
+        const int nsym = n_bits / m;
+        for (int idx = tid; idx < kHeadIpb * nsym; idx += 256) {
+            const int i = idx / nsym, j = idx - i * nsym;
+            if (n0 + i < n_img) {
+                int sym = 0;
+                for (int u = 0; u < m; ++u) sym |= (int)sbit[i][j * m + u] << (m - 1 - u);
+                symbols[(n0 + i) * nsym + j] = (uint8_t)sym;
+            }
         }
     }
 }
@@ -490,28 +851,67 @@ int persistent_blocks(int num_cu, int per_cu, int64_t work)
 } // namespace
 
 hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
-                             bf16_t *out, int num_cu, hipStream_t s)
+                             float *tout, const Partition &part, bf16_t *out, hipStream_t s)
 {
-    const int64_t items = (int64_t)g.n_img * g.h * ((g.w + 31) / 32);
-    const int blocks = persistent_blocks(num_cu, 8, (items + 3) / 4);
     if (C == 64)
-        hipLaunchKernelGGL(conv_first_kernel<64>, dim3(blocks), dim3(256), 0, s, src, g, wfrag, bias, out);
+        hipLaunchKernelGGL(conv_first_kernel<64>, dim3(part.blocks), dim3(256), 0, s, src, g, wfrag, bias, tout,
+                           part.slots, part.per, out);
     else
-        hipLaunchKernelGGL(conv_first_kernel<32>, dim3(blocks), dim3(256), 0, s, src, g, wfrag, bias, out);
+        hipLaunchKernelGGL(conv_first_kernel<32>, dim3(part.blocks), dim3(256), 0, s, src, g, wfrag, bias, tout,
+                           part.slots, part.per, out);
     return hipGetLastError();
 }
 
 hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
-                           const float *bias, bf16_t *out, int num_cu, hipStream_t s)
+                           const float *bias, const float *tin, int in_slots, const float *rsum, float *tout,
+                           const Partition &part, bool last, bf16_t *out, hipStream_t s)
 {
-    const int64_t tiles = (int64_t)g.n_img * g.strips * g.colblks;
-    const int blocks = persistent_blocks(num_cu, 2, tiles);
-    if (C == 64)
-        hipLaunchKernelGGL(conv_mid_kernel<64>, dim3(blocks), dim3(256), 0, s, ws, in_off, g, wfrag, bias, out);
-    else
-        hipLaunchKernelGGL(conv_mid_kernel<32>, dim3(blocks), dim3(256), 0, s, ws, in_off, g, wfrag, bias, out);
+    StatArgs st{tin, in_slots, rsum, tout, part.slots, part.per};
+    const dim3 grid(part.blocks), block(256);
+    if (C == 64) {
+        if (last) hipLaunchKernelGGL((conv_mid_kernel<64, MODE_LAST>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
+        else hipLaunchKernelGGL((conv_mid_kernel<64, MODE_MID>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
+    } else {
+        if (last) hipLaunchKernelGGL((conv_mid_kernel<32, MODE_LAST>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
+        else hipLaunchKernelGGL((conv_mid_kernel<32, MODE_MID>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
+    }
     return hipGetLastError();
 }
+
+hipError_t launch_head(const float *recs, int slots, int C, int64_t n_img, int n_bits, int nbp, float inv_hw,
+                       const float *wft, const float *fbias, const float *lin_w, const float *lin_b, float *logits,
+                       uint8_t *bits, uint8_t *symbols, int m, hipStream_t s)
+{
+    if (n_img <= 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((n_img + kHeadIpb - 1) / kHeadIpb);
+    hipLaunchKernelGGL(head_kernel, dim3(blocks), dim3(256), 0, s, recs, slots, C, (int)n_img, n_bits, nbp, inv_hw, wft,
+                       fbias, lin_w, lin_b, logits, bits, symbols, m);
+    return hipGetLastError();
+}
+
+// Tiles are dealt to workgroups in contiguous runs of `per`; `per` divides the tiles of one image or is
+// a multiple of them, so a workgroup never holds two partial images and an image is touched by exactly
+// `slots` workgroups.
+Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks)
+{
+    Partition p{};
+    const int64_t total = n_img * tiles_per_image;
+    int64_t want = (total + target_blocks - 1) / target_blocks;
+    if (want < 1) want = 1;
+    if (want >= tiles_per_image) {
+        p.per = (int)((want + tiles_per_image - 1) / tiles_per_image) * tiles_per_image;
+        p.slots = 1;
+    } else {
+        int d = (int)want;
+        while (tiles_per_image % d) ++d;
+        p.per = d;
+        p.slots = tiles_per_image / d;
+    }
+    p.blocks = (int)((total + p.per - 1) / p.per);
+    return p;
+}
+
+size_t stat_record_floats(int C, int nq) { return (size_t)stat_rec(C, nq); }
 
 hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
                              const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,

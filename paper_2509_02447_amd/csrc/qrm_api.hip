@@ -58,6 +58,9 @@ struct qrm_ctx {
     const float *d_bias = nullptr;        // [n_blocks*C]
     const float *d_bias_final = nullptr;  // [nbp] or null
     const float *d_lin_w = nullptr, *d_lin_b = nullptr;
+    const float *d_rsum = nullptr;        // [(n_blocks-1)][C][C] weight-rounding residual sums of the C -> C layers
+    const float *d_wft = nullptr;         // final conv, fp32, [C*9][nbp]
+    bool collapse = false;                // final conv + pool evaluated in closed form from channel sums
     // code
     RsParams rs{};
     void *d_tables = nullptr;
@@ -104,19 +107,46 @@ void pack_mid(const float *w, const float *scale, int cout, int cout_pad, int ci
                     }
 }
 
-// first layer: k = kc*16 + (lane/32)*8 + e, k < 27 -> tap = k/3, channel = k%3
+// first layer: k = q*16 + (lane/32)*8 + e  ->  tap = k/4 (0..8, beyond: zero), channel = k%4 (3: zero).
+// Per output block two fragment sets: bf16(w) and bf16(w - bf16(w)).
+float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
 void pack_first(const float *w, const float *scale, int cout, std::vector<uint16_t> &dst)
 {
     for (int blk = 0; blk < cout / 32; ++blk)
-        for (int kc = 0; kc < 2; ++kc)
-            for (int lane = 0; lane < 64; ++lane)
-                for (int e = 0; e < 8; ++e) {
-                    const int o = blk * 32 + perm32(lane & 31);
-                    const int k = kc * 16 + (lane >> 5) * 8 + e;
-                    float v = 0.f;
-                    if (k < 27) v = w[((size_t)o * 3 + k % 3) * 9 + k / 3] * (scale ? scale[o] : 1.f);
-                    dst.push_back(f32_to_bf16_rne(v));
-                }
+        for (int part = 0; part < 2; ++part)
+            for (int q = 0; q < 3; ++q)
+                for (int lane = 0; lane < 64; ++lane)
+                    for (int e = 0; e < 8; ++e) {
+                        const int o = blk * 32 + perm32(lane & 31);
+                        const int k = q * 16 + (lane >> 5) * 8 + e;
+                        const int tap = k / 4, ch = k % 4;
+                        float v = 0.f;
+                        if (tap < 9 && ch < 3) v = w[((size_t)o * 3 + ch) * 9 + tap] * (scale ? scale[o] : 1.f);
+                        const uint16_t hi = f32_to_bf16_rne(v);
+                        dst.push_back(part == 0 ? hi : f32_to_bf16_rne(v - bf16_to_f32(hi)));
+                    }
+}
+
+// rsum[o][c] = sum over the 9 taps of (w*scale - bf16(w*scale)): what the bf16 weights leave out, as it
+// acts on a spatially constant input
+void residual_sums(const float *w, const float *scale, int C, std::vector<float> &dst)
+{
+    for (int o = 0; o < C; ++o)
+        for (int ci = 0; ci < C; ++ci) {
+            double r = 0.0;
+            for (int tap = 0; tap < 9; ++tap) {
+                const float v = w[((size_t)o * C + ci) * 9 + tap] * (scale ? scale[o] : 1.f);
+                r += (double)v - (double)bf16_to_f32(f32_to_bf16_rne(v));
+            }
+            dst.push_back((float)r);
+        }
 }
 
 int default_micro_batch(const qrm_ctx *c, int h, int w)
@@ -140,9 +170,13 @@ int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w)
 }
 
 struct WsLayout {
-    size_t act, partial, symbols, total;
+    size_t act, partial, stats, symbols, total;
     int mb, n_part;
 };
+
+int tiles_per_image(int h, int w) { return ((h + kRows - 1) / kRows) * ((w + kTileW - 1) / kTileW); }
+int first_blocks(const qrm_ctx *c) { return 8 * c->num_cu; }
+int mid_blocks(const qrm_ctx *c) { return 2 * c->num_cu; }
 
 WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
 {
@@ -152,9 +186,20 @@ WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
         L.n_part = ((w + kTileW - 1) / kTileW) * 2;
         L.act = align_up((size_t)L.mb * h * w * c->C * 2);
         L.partial = align_up((size_t)L.mb * L.n_part * c->nbp * 4);
+        // statistics records: sized for the fullest micro-batch and for the ragged last one
+        const int tpi = tiles_per_image(h, w);
+        size_t recs = 0;
+        const int64_t counts[2] = {L.mb, N % L.mb};
+        for (int64_t cnt : counts) {
+            if (cnt <= 0) continue;
+            const Partition pf = make_partition(cnt, tpi, first_blocks(c)), pm = make_partition(cnt, tpi, mid_blocks(c));
+            const size_t r = (size_t)cnt * (pf.slots > pm.slots ? pf.slots : pm.slots);
+            if (r > recs) recs = r;
+        }
+        L.stats = align_up(recs * stat_record_floats(c->C, 9) * 4);
     }
     L.symbols = (want_symbols && c->has_rs) ? align_up((size_t)N * c->rs.n) : 0;
-    L.total = kZeroBytes + 2 * L.act + L.partial + L.symbols;
+    L.total = kZeroBytes + 2 * L.act + L.partial + 2 * L.stats + L.symbols;
     return L;
 }
 
@@ -200,17 +245,22 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
     const uint32_t buf_off[2] = {(uint32_t)kZeroBytes, (uint32_t)(kZeroBytes + L.act)};
     bf16_t *buf[2] = {(bf16_t *)(base + buf_off[0]), (bf16_t *)(base + buf_off[1])};
     float *partial = (float *)(base + kZeroBytes + 2 * L.act);
+    float *tb[2] = {(float *)(base + kZeroBytes + 2 * L.act + L.partial),
+                    (float *)(base + kZeroBytes + 2 * L.act + L.partial + L.stats)};
     const int nsym = (d_symbols && m_sym > 0) ? c->n_bits / m_sym : 0;
     const uint8_t *img0 = src.img;
     const int32_t *off0 = src.off;
+    const int tpi = tiles_per_image(h, w);
+    const float inv_hw = 1.0f / ((float)h * (float)w);
     hipError_t e;
     for (int64_t n0 = 0; n0 < N; n0 += L.mb) {
         const int cnt = (int)((N - n0 < L.mb) ? (N - n0) : L.mb);
         ConvGeom g{cnt, h, w, (h + kRows - 1) / kRows, (w + kTileW - 1) / kTileW};
+        const Partition pf = make_partition(cnt, tpi, first_blocks(c)), pm = make_partition(cnt, tpi, mid_blocks(c));
         src.img = img0 + n0 * 3 * (int64_t)src.H * src.W;
         src.off = off0 ? off0 + 2 * n0 : nullptr;
-        int cur = 0;
-        e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, buf[cur], c->num_cu, s);
+        int cur = 0, tcur = 0, in_slots = pf.slots;
+        e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
         if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
         const int blocks = n_run > 0 ? n_run : c->n_blocks;
         for (int b = 1; b < blocks; ++b) {
@@ -229,29 +279,40 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
                 c->ev_used += 2;
                 (void)hipEventRecord(ev0, s);
             }
-            e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C,
-                                buf[cur ^ 1], c->num_cu, s);
+            const bool last = n_run < 0 && c->collapse && b == c->n_blocks - 1;
+            e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C, tb[tcur],
+                                in_slots, c->d_rsum + (size_t)(b - 1) * c->C * c->C, tb[tcur ^ 1], pm, last,
+                                buf[cur ^ 1], s);
             if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
             if (c->profile) {
                 (void)hipEventRecord(ev1, s);
                 c->prof_flops += 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
             }
             cur ^= 1;
+            tcur ^= 1;
+            in_slots = pm.slots;
         }
         if (n_run > 0) {
             e = launch_nhwc_to_nchw(buf[cur], cnt, h, w, c->C, d_act + n0 * (int64_t)c->C * h * w, s);
             if (e != hipSuccess) return hip_fail(c, e, "nhwc_to_nchw launch");
             continue;
         }
-        e = launch_conv_final(base, buf_off[cur], g, c->C, c->nbp, c->d_w_final, c->d_bias_final, c->final_relu,
-                              partial, c->num_cu, s);
-        if (e != hipSuccess) return hip_fail(c, e, "conv_final launch");
-        e = launch_linear_pack(partial, L.n_part, c->nbp, cnt, c->n_bits, 1.0f / ((float)h * (float)w),
-                               c->final_relu ? nullptr : c->d_bias_final, c->d_lin_w, c->d_lin_b,
-                               d_logits ? d_logits + n0 * c->n_bits : nullptr,
-                               d_bits ? d_bits + n0 * c->n_bits : nullptr,
-                               nsym ? d_symbols + n0 * nsym : nullptr, m_sym > 0 ? m_sym : 1, s);
-        if (e != hipSuccess) return hip_fail(c, e, "linear_pack launch");
+        float *lg = d_logits ? d_logits + n0 * c->n_bits : nullptr;
+        uint8_t *bt = d_bits ? d_bits + n0 * c->n_bits : nullptr;
+        uint8_t *sy = nsym ? d_symbols + n0 * nsym : nullptr;
+        if (c->collapse) {
+            e = launch_head(tb[tcur], in_slots, c->C, cnt, c->n_bits, c->nbp, inv_hw, c->d_wft, c->d_bias_final,
+                            c->d_lin_w, c->d_lin_b, lg, bt, sy, m_sym > 0 ? m_sym : 1, s);
+            if (e != hipSuccess) return hip_fail(c, e, "head launch");
+        } else {
+            e = launch_conv_final(base, buf_off[cur], g, c->C, c->nbp, c->d_w_final, c->d_bias_final, c->final_relu,
+                                  partial, c->num_cu, s);
+            if (e != hipSuccess) return hip_fail(c, e, "conv_final launch");
+            e = launch_linear_pack(partial, L.n_part, c->nbp, cnt, c->n_bits, inv_hw,
+                                   c->final_relu ? nullptr : c->d_bias_final, c->d_lin_w, c->d_lin_b, lg, bt, sy,
+                                   m_sym > 0 ? m_sym : 1, s);
+            if (e != hipSuccess) return hip_fail(c, e, "linear_pack launch");
+        }
     }
     return QRM_OK;
 }
@@ -340,7 +401,8 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         frag_off.push_back(frag.size());
         pack_mid(w, c->final_affine ? ext->scale + (size_t)nb * C : nullptr, nbits, nbp, C, frag);
 
-        std::vector<float> fl; // biases [nb*C], final bias [nbp], lin_w, lin_b
+        c->collapse = nb >= 2 && !c->final_relu;
+        std::vector<float> fl; // biases [nb*C], final bias [nbp], lin_w, lin_b, residual sums, final conv (fp32)
         for (int i = 0; i < nb * C; ++i) fl.push_back(ext->bias ? ext->bias[i] : 0.f);
         const size_t off_fb = fl.size();
         for (int i = 0; i < nbp; ++i) fl.push_back((c->final_affine && i < nbits) ? ext->bias[(size_t)nb * C + i] : 0.f);
@@ -348,6 +410,23 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         for (int i = 0; i < nbits * nbits; ++i) fl.push_back(ext->lin_w[i]);
         const size_t off_lb = fl.size();
         for (int i = 0; i < nbits; ++i) fl.push_back(ext->lin_b ? ext->lin_b[i] : 0.f);
+        while (fl.size() % 4) fl.push_back(0.f);
+        const size_t off_rs = fl.size();
+        {
+            const float *wm = ext->conv_w + (size_t)C * 3 * 9;
+            for (int b = 1; b < nb; ++b) {
+                residual_sums(wm, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, fl);
+                wm += (size_t)C * C * 9;
+            }
+        }
+        const size_t off_wft = fl.size();
+        {
+            const float *wf = ext->conv_w + (size_t)C * 3 * 9 + (size_t)(nb - 1) * C * C * 9;
+            for (int k = 0; k < C * 9; ++k)          // k = c*9 + tap, the OIHW order within one output
+                for (int o = 0; o < nbp; ++o)
+                    fl.push_back(o < nbits ? wf[(size_t)o * C * 9 + k] * (c->final_affine ? ext->scale[(size_t)nb * C + o] : 1.f)
+                                           : 0.f);
+        }
 
         const size_t frag_bytes = align_up(frag.size() * 2);
         const size_t total = frag_bytes + align_up(fl.size() * 4);
@@ -366,6 +445,8 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         c->d_bias_final = c->final_affine ? flb + off_fb : nullptr;
         c->d_lin_w = flb + off_lw;
         c->d_lin_b = flb + off_lb;
+        c->d_rsum = flb + off_rs;
+        c->d_wft = flb + off_wft;
     }
     if (rs) {
         c->has_rs = true;
@@ -529,7 +610,7 @@ qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H,
     Slot *slot = nullptr;
     qrm_status st = get_slot(c, s, L.total, &slot);
     if (st != QRM_OK) return st;
-    uint8_t *d_sym = (uint8_t *)slot->ws + kZeroBytes + 2 * L.act + L.partial;
+    uint8_t *d_sym = (uint8_t *)slot->ws + kZeroBytes + 2 * L.act + L.partial + 2 * L.stats;
     TileSrc src{d_images, d_off_yx, H, W, {c->mean[0], c->mean[1], c->mean[2]},
                 {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
     st = run_extractor(c, slot, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, s);

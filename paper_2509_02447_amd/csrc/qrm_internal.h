@@ -41,15 +41,35 @@ struct TileSrc {
 hipError_t launch_extract_tiles(const uint8_t *img, int64_t N, int H, int W, const int32_t *off, int tile,
                                 uint8_t *out, hipStream_t s);
 
-// conv1: crop + normalise + conv3x3 (3 -> C) + bias + ReLU -> bf16 NHWC
+// How the tiles of a launch are dealt to workgroups (see make_partition).
+struct Partition {
+    int per;    // tiles per workgroup
+    int slots;  // workgroups that touch one image = statistics records per image
+    int blocks; // grid size
+};
+Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks);
+size_t stat_record_floats(int C, int nq); // floats per statistics record holding nq sums per channel
+
+// conv1: crop + normalise + conv3x3 (3 -> C, bf16 high + residual weights) + bias + ReLU -> bf16 NHWC;
+// tout (optional): sampled channel sums of the output, [n_img][part.slots][stat_record_floats(C,1)]
 hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
-                             bf16_t *out, int num_cu, hipStream_t s);
+                             float *tout, const Partition &part, bf16_t *out, hipStream_t s);
 
 // conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out.  The input is addressed as ws + in_off (+ 32-bit
 // offsets); the first kZeroBytes of ws must be zero: they are the source of the zero padding.
+// tin / in_slots / rsum: channel sums of the input and the summed weight-rounding residual [C][C] used
+// to correct the bias (either may be null).  tout: statistics of the output.  last: no activations are
+// written, tout receives the nine border-aware sums per channel (stat_record_floats(C,9) per record).
 constexpr size_t kZeroBytes = 256;
 hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
-                           const float *bias, bf16_t *out, int num_cu, hipStream_t s);
+                           const float *bias, const float *tin, int in_slots, const float *rsum, float *tout,
+                           const Partition &part, bool last, bf16_t *out, hipStream_t s);
+
+// nine channel sums of the last block -> final conv + average pool in closed form -> linear -> logits,
+// bits, symbols.  wft: final conv weights fp32, [C*9][nbp] (k = c*9 + tap major)
+hipError_t launch_head(const float *recs, int slots, int C, int64_t n_img, int n_bits, int nbp, float inv_hw,
+                       const float *wft, const float *fbias, const float *lin_w, const float *lin_b, float *logits,
+                       uint8_t *bits, uint8_t *symbols, int m, hipStream_t s);
 
 // final conv3x3 C -> nbp (n_bits padded to 32s) (+bias, optional ReLU) + sum over pixels -> partial sums
 // partial: f32 [n_img][colblks*2][nbp]
