@@ -40,6 +40,9 @@ def main() -> int:
     ap.add_argument("--micro-batch", type=int, default=0)
     ap.add_argument("--cpu-sample", type=int, default=48, help="images the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--policy", default="random", choices=["random", "random_grid", "fixed"])
+    ap.add_argument("--calibration-copy", type=int, default=0,
+                    help="MiB of a plain device-to-device copy issued once before the timed region: the kernel of "
+                         "known size that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one device); --gpus must be 1. "
@@ -82,6 +85,12 @@ def main() -> int:
     def step():
         ctx.qrm_detect(d_img, N, cfg.H, cfg.W, d_off, cfg.tile, d_logits, d_bits, d_msg, d_cw, d_ne, stream=stream)
 
+    if args.calibration_copy:
+        cal_src = torch.zeros(args.calibration_copy << 20, dtype=torch.uint8, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+        cal_dst.copy_(cal_src)
+        torch.cuda.synchronize()
+        del cal_src, cal_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -13,7 +13,8 @@ import numpy as np
 QRM_OK, QRM_E_INVALID, QRM_E_UNSUPPORTED, QRM_E_NOMEM, QRM_E_DEVICE = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libqrm.so")
+# QRM_LIBRARY selects another build of the same library (same ABI), e.g. one with different tuning constants
+_LIB_PATH = os.environ.get("QRM_LIBRARY") or os.path.join(_HERE, "libqrm.so")
 _lib = None
 
 
