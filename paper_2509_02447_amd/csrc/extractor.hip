@@ -86,82 +86,119 @@ struct MidCfg {
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
+typedef const __attribute__((address_space(3))) uint8_t *lrow_t; // 32-bit LDS address
 
 // Asynchronous staging of one strip (kRows + 2 rows, halo included) into LDS with direct-to-LDS loads.
 // A staged row is cut into PIECES pieces of 64 slots of 16 bytes; one wavefront-wide load fills one
 // piece (1 KiB of LDS at row*ROWB + piece*1024), lane l supplying slot piece*64 + l = (column, 8-channel
 // chunk).  Wavefront w always handles pieces w, w+4, ..., so the per-lane column decoding is done once
-// per strip, not once per load.  Pad slots and pixels outside the tile read from the block of zeros
-// that opens the workspace (offset 0 from `ws`): that is the zero padding of the convolution.  All
+// per strip, not once per load.  Lanes whose slot is padding never load (their LDS bytes are never
+// read).  Pixels outside the tile must read as zero (zero padding of the convolution): rows above /
+// below the tile load from the block of zeros that opens the workspace (offset 0 from `ws`); halo
+// columns do the same, except when the tile is a single column block: then those LDS columns are never
+// written at all and keep the zeros the kernel put there at start (`halo_cols_prezeroed`).  All
 // sources are addressed as ws + 32-bit byte offset.  The caller waits with s_waitcnt vmcnt(0) and a
 // barrier before reading the strip.
+constexpr uint32_t kSlotSkip = 0xffffffffu; // lane does not load
+constexpr uint32_t kSlotZero = 0xfffffffeu; // lane loads zeros
+
 template <int C>
 __device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *ws, uint32_t img_off, int h, int w,
-                                                  int y0, int x0, int wave, int lane)
+                                                  int y0, int x0, bool halo_cols_prezeroed, int wave, int lane,
+                                                  int first_row = 0, int rot = 0)
 {
     typedef MidCfg<C> K;
-    uint32_t coff[K::QPW]; // byte offset of this lane's slot inside an image row, or ~0u for "zeros"
+    uint32_t coff[K::QPW]; // byte offset of this lane's slot inside an image row, or one of the two marks
 #pragma unroll
     for (int qi = 0; qi < K::QPW; ++qi) {
         const int slot = (wave + 4 * qi) * 64 + lane;
         const int col = slot / K::SPP, cpos = slot - col * K::SPP;
         const int gx = x0 - 1 + col;
-        const bool ok = cpos < C / 8 && col < kHaloW && gx >= 0 && gx < w;
-        coff[qi] = ok ? (uint32_t)((gx * C + cpos * 8) * 2) : ~0u;
+        uint32_t c = kSlotSkip;
+        if (cpos < C / 8 && col < kHaloW) {
+            if (gx >= 0 && gx < w) c = (uint32_t)((gx * C + cpos * 8) * 2);
+            else if (!halo_cols_prezeroed) c = kSlotZero;
+        }
+        coff[qi] = c;
     }
 #pragma unroll
     for (int r = 0; r < kRows + 2; ++r) {
+        if (r < 2 && r < first_row) continue;                       // still in LDS from the previous strip
         const int gy = y0 - 1 + r;                                  // same for the whole workgroup
         const bool rowok = gy >= 0 && gy < h;
+        const int rslot = rot + r >= kRows + 2 ? rot + r - (kRows + 2) : rot + r;
         const uint32_t rowoff = img_off + (uint32_t)(gy * w * C * 2);
 #pragma unroll
         for (int qi = 0; qi < K::QPW; ++qi) {
             const int q = wave + 4 * qi;                            // same for the whole wavefront
-            if (q < K::PIECES) {
-                const uint32_t off = (rowok && coff[qi] != ~0u) ? rowoff + coff[qi] : 0u;
-                __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + r * K::ROWB + q * 1024), 16, 0, 0);
+            if (4 * qi + 3 < K::PIECES || q < K::PIECES) {
+                {
+                    const uint32_t off = (rowok && coff[qi] < kSlotZero) ? rowoff + coff[qi] : 0u;
+                    __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + rslot * K::ROWB + q * 1024), 16, 0,
+                                                     0);
+                }
             }
         }
     }
 }
 
-// Accumulates RW output rows of one 32-pixel x 32-channel block from the staged strip.  Fragments are
-// read one (input row, horizontal tap) group ahead of the matrix instructions that consume them; each
-// fragment feeds the up to three vertical taps that touch its input row.
+// the strip buffer starts as zeros (see issue_strip_loads)
+template <int C>
+__device__ __forceinline__ void zero_strip_buffer(uint8_t *lds, int tid)
+{
+    typedef MidCfg<C> K;
+    for (int i = tid * 16; i < K::LDS_BYTES; i += 256 * 16) *(u32x4 *)(lds + i) = (u32x4){0u, 0u, 0u, 0u};
+}
+
+// Accumulates RW output rows of one 32-pixel x 32-channel block from the staged strip.
+//
+// The RW + 2 staged rows feed 1, 2, 3, .., 3, 2, 1 vertical taps; rows are paired (p, p + (RW+2)/2) so
+// that every pair feeds the same number of matrix instructions.  A "set" is the four fragments
+// {two rows of a pair} x {two 16-channel k chunks} of one horizontal tap: 8 (RW = 4) matrix
+// instructions.  Each fragment register is refilled for set s+1 right after the matrix instructions of
+// set s that read it, and the scheduler is fenced so that it keeps that order: every LDS read has the
+// matrix instructions of the three other fragments (6 x 32 cycles at RW = 4) to land.
 // POOL: all rows are summed into acc[0] / acc[1] (global average pool of the last layer); rows at or
 // beyond `rows_valid` are skipped (RAGGED: the last strip of a tile whose height is not a multiple of kRows).
 template <int C, int RW, bool POOL, bool RAGGED = false>
-__device__ __forceinline__ void strip_mma(const uint8_t *lbase, const bf16x8 (&Wr)[9][C / 16], f32x16 *acc,
-                                          int rows_valid)
+__device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf16x8 (&Wr)[9][C / 16],
+                                          f32x16 *acc, int rows_valid)
 {
     typedef MidCfg<C> K;
-    constexpr int NG = (RW + 2) * 3;
-    bf16x8 f[2][K::KC];
+    constexpr int NP = (RW + 2) / 2;  // row pairs
+    constexpr int KP = K::KC / 2;     // pairs of k chunks
+    constexpr int NS = 3 * KP * NP;   // sets
+    bf16x8 f[4];
+    auto set_row = [](int s2, int j) { return (s2 % NP) + (j & 1) * NP; };
+    auto set_kc = [](int s2, int j) { return 2 * ((s2 / NP) % KP) + (j >> 1); };
+    auto set_dx = [](int s2) { return s2 / (NP * KP); };
+    auto frag = [&](int s2, int j) {
+        return *(const __attribute__((address_space(3))) bf16x8 *)(rowp[set_row(s2, j)] + set_dx(s2) * K::PS +
+                                                                   set_kc(s2, j) * 32);
+    };
 #pragma unroll
-    for (int kc = 0; kc < K::KC; ++kc) f[0][kc] = *(const bf16x8 *)(lbase + kc * 32);
+    for (int j = 0; j < 4; ++j) f[j] = frag(0, j);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-        const int r = g / 3, dx = g % 3;
-        if (g + 1 < NG) {
-            const int r2 = (g + 1) / 3, dx2 = (g + 1) % 3;
+    for (int s2 = 0; s2 < NS; ++s2) {
+        const int dx = set_dx(s2);
 #pragma unroll
-            for (int kc = 0; kc < K::KC; ++kc)
-                f[(g + 1) & 1][kc] = *(const bf16x8 *)(lbase + r2 * K::ROWB + dx2 * K::PS + kc * 32);
-        }
-#pragma unroll
-        for (int kc = 0; kc < K::KC; ++kc) {
+        for (int j = 0; j < 4; ++j) {
+            const int r = set_row(s2, j), kc = set_kc(s2, j);
 #pragma unroll
             for (int dy = 0; dy < 3; ++dy) {
                 const int orow = r - dy;
                 if (orow >= 0 && orow < RW) {
                     if (POOL) {
-                        if (!RAGGED || orow < rows_valid)
-                            acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], f[g & 1][kc], acc[orow & 1]);
+                        if (!RAGGED || orow < rows_valid) acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow & 1]);
                     } else {
-                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[g & 1][kc], acc[orow]);
+                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow]);
                     }
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s2 + 1 < NS) f[j] = frag(s2 + 1, j); // register j is free again: refill it for the next set
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -192,10 +229,22 @@ __device__ __forceinline__ void load_weight_frags(bf16x8 (&Wr)[9][C / 16], const
 constexpr int kStatPad = 16;
 __host__ __device__ constexpr int stat_rec(int C, int nq) { return nq * C + kStatPad; }
 
-__device__ __forceinline__ float half_sum(float v) // over the 32 pixel lanes of one half-wavefront
+// Sum over the 32 pixel lanes of one half-wavefront with DPP lane permutes (no LDS traffic, no waits).
+// After the four butterfly steps every lane holds the sum of its row of 16 lanes; the last step adds the
+// sum of row 0 (2) into row 1 (3).  The total is valid in lanes with px >= 16 only: kSumLane reads it.
+constexpr int kSumLane = 16;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float v)
 {
-#pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) v += __shfl_xor(v, off, 32);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float half_sum(float v)
+{
+    v += dpp_f<0xB1, 0xf>(v);  // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E, 0xf>(v);  // quad_perm [2,3,0,1]
+    v += dpp_f<0x141, 0xf>(v); // row_half_mirror
+    v += dpp_f<0x140, 0xf>(v); // row_mirror
+    v += dpp_f<0x142, 0xa>(v); // row_bcast:15 into rows 1 and 3
     return v;
 }
 
@@ -221,7 +270,7 @@ struct StatArgs {
     int per;            // tiles per workgroup: divides, or is a multiple of, the tiles of one image
 };
 
-constexpr int MODE_MID = 0;  // write activations, sample channel sums from every fourth strip
+constexpr int MODE_MID = 0;  // write activations, sample channel sums from every eighth strip
 constexpr int MODE_LAST = 1; // last block: no activations, the nine border-aware channel sums
 
 // C -> C (+bias, ReLU), bf16 NHWC in / out.  Two workgroups per CU: while one waits for its strip to
@@ -260,15 +309,21 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
     const int t_begin = vb * st.per;
     const int t_end = min(total, t_begin + st.per);
     const int out_slot = st.per >= tpi ? 0 : (t_begin % tpi) / st.per;
-    const uint8_t *lbase = lds + (rg * RW) * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
+    const uint8_t *lbase = lds + (xb * 32 + px) * K::PS + half * 16;
     float *my_stat = &s_stat[wave][0][half * 16];
 
+    // tile order: image, column block, strip - consecutive tiles of a workgroup are vertically adjacent
+    // strips, which share two staged rows
     auto decode = [&](int t, int &n, int &strip, int &x0) {
-        const int colblk = t % g.colblks;
-        strip = (t / g.colblks) % g.strips;
+        strip = t % g.strips;
+        const int colblk = (t / g.strips) % g.colblks;
         n = t / tpi;
         x0 = colblk * kTileW;
     };
+    // The kRows + 2 row slots of the strip buffer form a ring: window row j of strip s (image row
+    // s*kRows - 1 + j) lives in slot (s*kRows + j) mod (kRows + 2), so the last two rows of a strip are
+    // already in place as the first two rows of the strip below it and only kRows rows are loaded.
+    auto ring_rot = [](int strip) { return (strip * kRows) % (kRows + 2); };
     auto zero_stats = [&]() {
         for (int i = tid; i < 4 * NQ * 32; i += 256) (&s_stat[0][0][0])[i] = 0.f;
         if (tid < 4) s_cnt[tid] = 0.f;
@@ -323,12 +378,16 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
         __syncthreads();
     };
 
+    const int sample_phase = min(3, g.strips - 1); // strips 3, 11, 19, .. are sampled (the last one of a short tile)
+    const bool prezero = g.colblks == 1;
+    zero_strip_buffer<C>(lds, tid);
     zero_stats();
+    __syncthreads();
     if (t_begin < t_end) {
         int n, strip, x0;
         decode(t_begin, n, strip, x0);
         issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, strip * kRows, x0,
-                             wave, lane);
+                             prezero, wave, lane, 0, ring_rot(strip));
     }
     int cur_n = -1;
     for (int t = t_begin; t < t_end; ++t) {
@@ -354,27 +413,33 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads(); // the strip has landed for every wavefront
-        strip_mma<C, RW, false>(lbase, Wr, acc, RW);
-        __syncthreads(); // everyone is done reading: the buffer may be refilled
+        {
+            lrow_t rowp[RW + 2];
+            const int start = ring_rot(strip) + rg * RW;
+#pragma unroll
+            for (int r = 0; r < RW + 2; ++r) rowp[r] = (lrow_t)lbase + ((start + r) % (kRows + 2)) * K::ROWB;
+            strip_mma<C, RW, false>(rowp, Wr, acc, RW);
+        }
+        __syncthreads(); // everyone is done reading: the rows no longer needed may be overwritten
         if (t + 1 < t_end) {
             int n2, strip2, x2;
             decode(t + 1, n2, strip2, x2);
+            const bool below = n2 == n && x2 == x0 && strip2 == strip + 1;
             issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n2 * (uint32_t)(g.h * g.w * C * 2), g.h, g.w,
-                                 strip2 * kRows, x2, wave, lane);
+                                 strip2 * kRows, x2, prezero, wave, lane, below ? 2 : 0, ring_rot(strip2));
         }
 
         const int x = x0 + xb * 32 + px;
         const int yw = y0 + rg * RW; // first output row of this wavefront
         if (MODE == MODE_MID) {
-            const int64_t img_base = (int64_t)n * g.h * g.w;
+            // element offset of this lane's first row; the activation buffer is below 2^31 elements
+            const uint32_t e0 = (uint32_t)(((n * g.h + yw) * g.w + x) * C + cb * 32 + half * 16);
 #pragma unroll
             for (int r = 0; r < RW; ++r) {
-                const int y = yw + r;
-                if (y < g.h && x < g.w)
-                    store_tile_bf16(out + (img_base + (int64_t)y * g.w + x) * C + cb * 32 + half * 16, acc[r], true);
+                if (yw + r < g.h && x < g.w) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
             }
         }
-        if (st.tout && (MODE == MODE_LAST || (strip & 3) == 0)) {
+        if (st.tout && (MODE == MODE_LAST || (strip & 7) == sample_phase)) {
             // per-lane sum over this wavefront's valid rows of relu(output)
             float tv[16];
 #pragma unroll
@@ -395,7 +460,7 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) tv[v] = half_sum(tv[v]);
-            lds_accumulate(my_stat, tv, px == 0);                    // whole tile (or its sampled strips)
+            lds_accumulate(my_stat, tv, px == kSumLane);                    // whole tile (or its sampled strips)
             if (cb == 0 && lane == 0) {
                 const int rows = max(0, min(RW, g.h - yw)), cols = max(0, min(32, g.w - (x0 + xb * 32)));
                 s_cnt[wave] += (float)(rows * cols);
@@ -409,7 +474,7 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
                     lds_accumulate(my_stat + 6 * 32, rv, x == g.w - 1);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
-                    lds_accumulate(my_stat + 1 * 32, rv, px == 0);
+                    lds_accumulate(my_stat + 1 * 32, rv, px == kSumLane);
                 }
                 const int rl = g.h - 1 - yw; // image row h-1 relative to this wavefront's rows
                 if (rl >= 0 && rl < RW) {
@@ -425,7 +490,7 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
                     lds_accumulate(my_stat + 8 * 32, rv, x == g.w - 1);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
-                    lds_accumulate(my_stat + 2 * 32, rv, px == 0);
+                    lds_accumulate(my_stat + 2 * 32, rv, px == kSumLane);
                 }
             }
         }
@@ -465,8 +530,12 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
     const int per = (total + nb - 1) / nb;
     const int t_begin = vb * per;
     const int t_end = min(total, t_begin + per);
-    const uint8_t *lbase = lds + (xb * 32 + px) * K::PS + half * 16;
+    lrow_t rowp[RW + 2];
+#pragma unroll
+    for (int r = 0; r < RW + 2; ++r) rowp[r] = (lrow_t)lds + r * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
     const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
+    const bool prezero = g.colblks == 1;
+    zero_strip_buffer<C>(lds, tid);
 
     for (int t = t_begin; t < t_end; ++t) {
         const int colblk = t % g.colblks;
@@ -479,29 +548,29 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
         for (int v = 0; v < 16; ++v) { sum[0][v] = 0.f; sum[1][v] = 0.f; }
 
         __syncthreads();
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, wave, lane);
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, prezero, wave, lane);
         for (int strip = 0; strip < g.strips; ++strip) {
             const int y0 = strip * kRows;
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             if (!RELU) {
-                if (g.h - y0 >= RW) strip_mma<C, RW, true, false>(lbase, Wr, sum, RW);
-                else strip_mma<C, RW, true, true>(lbase, Wr, sum, g.h - y0);
+                if (g.h - y0 >= RW) strip_mma<C, RW, true, false>(rowp, Wr, sum, RW);
+                else strip_mma<C, RW, true, true>(rowp, Wr, sum, g.h - y0);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave,
-                                         lane);
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, prezero,
+                                         wave, lane);
             } else {
                 f32x16 acc[RW];
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[r][v] = bias16[v];
-                strip_mma<C, RW, false>(lbase, Wr, acc, RW);
+                strip_mma<C, RW, false>(rowp, Wr, acc, RW);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave,
-                                         lane);
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, prezero,
+                                         wave, lane);
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
                     if (y0 + r < g.h)
@@ -647,7 +716,7 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
         }
         __syncthreads();
 
-        const bool sample = tout && (strip & 3) == 0;
+        const bool sample = tout && (strip & 7) == min(3, g.strips - 1);
 #pragma unroll
         for (int rr = 0; rr < NCB; ++rr) {
             const int row = rbase + rr;
@@ -677,7 +746,7 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
                     float tv[16];
 #pragma unroll
                     for (int v = 0; v < 16; ++v) tv[v] = half_sum(x < g.w ? fmaxf(acc[v], 0.f) : 0.f);
-                    lds_accumulate(&s_stat[wave][half * 16], tv, px == 0);
+                    lds_accumulate(&s_stat[wave][half * 16], tv, px == kSumLane);
                     if (cb == 0 && lane == 0) s_cnt[wave] += (float)max(0, min(32, g.w - (x0 + xb * 32)));
                 }
             }
