@@ -42,6 +42,25 @@ __device__ __forceinline__ int xcd_virtual_block(int b, int nblocks)
     return (b % 8) * (nblocks / 8) + b / 8;
 }
 
+// s_waitcnt immediates (gfx9 layout: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14]).  kWaitVm0
+// waits for vmcnt(0) only, OR-ing in n <= 15 gives vmcnt(n); kWaitLgkm0 waits for lgkmcnt(0) only.  The
+// builtin, unlike an asm statement, is seen by the compiler's own wait-count bookkeeping, which then does
+// not add a full drain of its own later.
+constexpr int kWaitVm0 = (7 << 4) | (15 << 8);
+constexpr int kWaitLgkm0 = 15 | (3 << 14) | (7 << 4);
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global store of the wavefront (a workgroup-scope fence counts direct-to-LDS loads as LDS writes and
+// drains the whole vector-memory queue), which would put the write latency of a strip's output on the
+// critical path of the next strip.  Callers wait for their direct-to-LDS loads themselves.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0); // own LDS reads / writes are done
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
@@ -86,7 +105,11 @@ struct MidCfg {
 
 typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
-typedef const __attribute__((address_space(3))) uint8_t *lrow_t; // 32-bit LDS address
+typedef uint32_t lrow_t; // LDS byte address
+__device__ __forceinline__ lrow_t lds_address(const void *p)
+{
+    return (lrow_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
+}
 
 // Asynchronous staging of one strip (kRows + 2 rows, halo included) into LDS with direct-to-LDS loads.
 // A staged row is cut into PIECES pieces of 64 slots of 16 bytes; one wavefront-wide load fills one
@@ -157,7 +180,10 @@ __device__ __forceinline__ void zero_strip_buffer(uint8_t *lds, int tid)
 // {two rows of a pair} x {two 16-channel k chunks} of one horizontal tap: 8 (RW = 4) matrix
 // instructions.  Each fragment register is refilled for set s+1 right after the matrix instructions of
 // set s that read it, and the scheduler is fenced so that it keeps that order: every LDS read has the
-// matrix instructions of the three other fragments (6 x 32 cycles at RW = 4) to land.
+// matrix instructions of the three other fragments (6 x 32 cycles at RW = 4) to land.  The reads and
+// their waits are written as assembly: the compiler, not knowing which direct-to-LDS load fills which
+// bytes, would otherwise drain the whole vector-memory queue (stores included) before the first read.
+// `rowp` holds the LDS byte address of each staged row for this lane.
 // POOL: all rows are summed into acc[0] / acc[1] (global average pool of the last layer); rows at or
 // beyond `rows_valid` are skipped (RAGGED: the last strip of a tile whose height is not a multiple of kRows).
 template <int C, int RW, bool POOL, bool RAGGED = false>
@@ -172,12 +198,12 @@ __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf
     auto set_row = [](int s2, int j) { return (s2 % NP) + (j & 1) * NP; };
     auto set_kc = [](int s2, int j) { return 2 * ((s2 / NP) % KP) + (j >> 1); };
     auto set_dx = [](int s2) { return s2 / (NP * KP); };
-    auto frag = [&](int s2, int j) {
-        return *(const __attribute__((address_space(3))) bf16x8 *)(rowp[set_row(s2, j)] + set_dx(s2) * K::PS +
-                                                                   set_kc(s2, j) * 32);
-    };
+#define QRM_FRAG_READ(dst, s2_, j_)                                                                         \
+    asm volatile("ds_read_b128 %0, %1 offset:%2"                                                            \
+                 : "=v"(dst)                                                                                \
+                 : "v"(rowp[set_row(s2_, j_)]), "n"(set_dx(s2_) * K::PS + set_kc(s2_, j_) * 32))
 #pragma unroll
-    for (int j = 0; j < 4; ++j) f[j] = frag(0, j);
+    for (int j = 0; j < 4; ++j) QRM_FRAG_READ(f[j], 0, j);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int s2 = 0; s2 < NS; ++s2) {
@@ -185,6 +211,10 @@ __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = set_row(s2, j), kc = set_kc(s2, j);
+            // LDS reads return in order: fragment j has landed once at most the three reads issued
+            // after it (none after the last set's) are outstanding
+            if (s2 + 1 < NS) asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(f[j]));
+            else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f[j]) : "n"(3 - j));
 #pragma unroll
             for (int dy = 0; dy < 3; ++dy) {
                 const int orow = r - dy;
@@ -197,10 +227,11 @@ __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (s2 + 1 < NS) f[j] = frag(s2 + 1, j); // register j is free again: refill it for the next set
+            if (s2 + 1 < NS) QRM_FRAG_READ(f[j], s2 + 1, j); // register j is free again: refill it for the next set
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+#undef QRM_FRAG_READ
 }
 
 template <int C>
@@ -375,6 +406,8 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
         } else if (tid < C) {
             s_init[tid] = bias[tid];
         }
+        // leave nothing in flight: the strip loop counts outstanding vector-memory operations
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
     };
 
@@ -389,7 +422,9 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
         issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, strip * kRows, x0,
                              prezero, wave, lane, 0, ring_rot(strip));
     }
+    __builtin_amdgcn_s_waitcnt(kWaitVm0); // weights (and the first strip) are in
     int cur_n = -1;
+    bool stores_behind_loads = false;
     for (int t = t_begin; t < t_end; ++t) {
         int n, strip, x0;
         decode(t, n, strip, x0);
@@ -411,16 +446,20 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
             }
         }
 
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads(); // the strip has landed for every wavefront
+        // Vector memory operations complete in issue order.  After a full strip every wavefront has issued
+        // its 2 * RW activation stores behind the loads of the next strip: waiting until at most that many
+        // operations are outstanding means the loads have landed, without waiting for the stores.
+        if (stores_behind_loads) __builtin_amdgcn_s_waitcnt(kWaitVm0 | (2 * RW));
+        else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        lds_barrier(); // the strip has landed for every wavefront
         {
             lrow_t rowp[RW + 2];
             const int start = ring_rot(strip) + rg * RW;
 #pragma unroll
-            for (int r = 0; r < RW + 2; ++r) rowp[r] = (lrow_t)lbase + ((start + r) % (kRows + 2)) * K::ROWB;
+            for (int r = 0; r < RW + 2; ++r) rowp[r] = lds_address(lbase) + ((start + r) % (kRows + 2)) * K::ROWB;
             strip_mma<C, RW, false>(rowp, Wr, acc, RW);
         }
-        __syncthreads(); // everyone is done reading: the rows no longer needed may be overwritten
+        lds_barrier(); // everyone is done reading: the rows no longer needed may be overwritten
         if (t + 1 < t_end) {
             int n2, strip2, x2;
             decode(t + 1, n2, strip2, x2);
@@ -434,10 +473,17 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
         if (MODE == MODE_MID) {
             // element offset of this lane's first row; the activation buffer is below 2^31 elements
             const uint32_t e0 = (uint32_t)(((n * g.h + yw) * g.w + x) * C + cb * 32 + half * 16);
+            const bool full = y0 + kRows <= g.h && x0 + kTileW <= g.w; // same for the whole workgroup
+            if (full) {
 #pragma unroll
-            for (int r = 0; r < RW; ++r) {
-                if (yw + r < g.h && x < g.w) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
+                for (int r = 0; r < RW; ++r) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
+            } else {
+#pragma unroll
+                for (int r = 0; r < RW; ++r) {
+                    if (yw + r < g.h && x < g.w) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
+                }
             }
+            stores_behind_loads = full;
         }
         if (st.tout && (MODE == MODE_LAST || (strip & 7) == sample_phase)) {
             // per-lane sum over this wavefront's valid rows of relu(output)
@@ -532,7 +578,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
     const int t_end = min(total, t_begin + per);
     lrow_t rowp[RW + 2];
 #pragma unroll
-    for (int r = 0; r < RW + 2; ++r) rowp[r] = (lrow_t)lds + r * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
+    for (int r = 0; r < RW + 2; ++r) rowp[r] = lds_address(lds) + r * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
     const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
     const bool prezero = g.colblks == 1;
     zero_strip_buffer<C>(lds, tid);
