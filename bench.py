@@ -26,8 +26,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# copy kernel of known size (see profiles/); None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# copy kernel of known size (profiles/conv_mid_c2_hbm_traffic.txt), for the default micro-batch of 256 images.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 274027688  # 133.13 MiB read + 128.20 MiB written; algorithmic 2 x 128 MiB
 
 
 def main() -> int:
