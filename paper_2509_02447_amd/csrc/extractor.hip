@@ -61,6 +61,14 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" ::: "memory");
 }
 
+// Passes a per-lane value through an empty asm statement: what is derived from the result is recomputed
+// where it is used instead of being hoisted and kept in registers across the matrix loop.
+__device__ __forceinline__ int pin_in_loop(int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
@@ -68,7 +76,8 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 // has its sign bit set, i.e. is negative as a 16-bit integer, so max(.,0) on the halves clamps it.
 __device__ __forceinline__ uint32_t pack_bf16_relu(float a, float b, bool relu)
 {
-    bf16x2 p = {(bf16_t)a, (bf16_t)b};
+    uint32_t p; // (the compiler would convert the two halves separately and merge them with a permute)
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(p) : "v"(a), "v"(b));
     s16x2 q = __builtin_bit_cast(s16x2, p);
     if (relu) q = __builtin_elementwise_max(q, (s16x2){0, 0});
     return __builtin_bit_cast(uint32_t, q);
@@ -111,66 +120,49 @@ __device__ __forceinline__ lrow_t lds_address(const void *p)
     return (lrow_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
 }
 
-// Asynchronous staging of one strip (kRows + 2 rows, halo included) into LDS with direct-to-LDS loads.
-// A staged row is cut into PIECES pieces of 64 slots of 16 bytes; one wavefront-wide load fills one
-// piece (1 KiB of LDS at row*ROWB + piece*1024), lane l supplying slot piece*64 + l = (column, 8-channel
-// chunk).  Wavefront w always handles pieces w, w+4, ..., so the per-lane column decoding is done once
-// per strip, not once per load.  Lanes whose slot is padding never load (their LDS bytes are never
-// read).  Pixels outside the tile must read as zero (zero padding of the convolution): rows above /
-// below the tile load from the block of zeros that opens the workspace (offset 0 from `ws`); halo
-// columns do the same, except when the tile is a single column block: then those LDS columns are never
-// written at all and keep the zeros the kernel put there at start (`halo_cols_prezeroed`).  All
-// sources are addressed as ws + 32-bit byte offset.  The caller waits with s_waitcnt vmcnt(0) and a
-// barrier before reading the strip.
-constexpr uint32_t kSlotSkip = 0xffffffffu; // lane does not load
-constexpr uint32_t kSlotZero = 0xfffffffeu; // lane loads zeros
+// Asynchronous staging of the rows of one strip (kRows + 2 rows, halo included) into LDS with
+// direct-to-LDS loads.  A staged row is cut into PIECES pieces of 64 slots of 16 bytes; one
+// wavefront-wide load fills one piece (1 KiB of LDS at slot*ROWB + piece*1024), lane l supplying slot
+// piece*64 + l = (column, 8-channel chunk).  Wavefront w (0..3) of the loading group always handles
+// pieces w, w+4, ..., so the per-lane column decoding is done once per strip, not once per load.
+// Pixels outside the tile must read as zero (zero padding of the convolution): rows above / below the
+// tile, halo columns outside it, and the padding slots of a pixel all load from the block of zeros that
+// opens the workspace (offset 0 from `ws`).  All sources are addressed as ws + 32-bit byte offset.
+// Window rows first_row..kRows+1 are loaded; window row r goes to row slot (ring_pos + r) mod nslot.
+// The caller waits (s_waitcnt vmcnt) and passes a barrier before anyone reads the rows.
+constexpr uint32_t kSlotZero = 0xffffffffu; // lane loads zeros
 
 template <int C>
 __device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *ws, uint32_t img_off, int h, int w,
-                                                  int y0, int x0, bool halo_cols_prezeroed, int wave, int lane,
-                                                  int first_row = 0, int rot = 0)
+                                                  int y0, int x0, int wave, int lane, int first_row = 0,
+                                                  int ring_pos = 0, int nslot = kRows + 2)
 {
     typedef MidCfg<C> K;
-    uint32_t coff[K::QPW]; // byte offset of this lane's slot inside an image row, or one of the two marks
+    uint32_t coff[K::QPW]; // byte offset of this lane's slot inside an image row, or the mark
 #pragma unroll
     for (int qi = 0; qi < K::QPW; ++qi) {
         const int slot = (wave + 4 * qi) * 64 + lane;
         const int col = slot / K::SPP, cpos = slot - col * K::SPP;
         const int gx = x0 - 1 + col;
-        uint32_t c = kSlotSkip;
-        if (cpos < C / 8 && col < kHaloW) {
-            if (gx >= 0 && gx < w) c = (uint32_t)((gx * C + cpos * 8) * 2);
-            else if (!halo_cols_prezeroed) c = kSlotZero;
-        }
-        coff[qi] = c;
+        coff[qi] = (cpos < C / 8 && col < kHaloW && gx >= 0 && gx < w) ? (uint32_t)((gx * C + cpos * 8) * 2) : kSlotZero;
     }
 #pragma unroll
     for (int r = 0; r < kRows + 2; ++r) {
-        if (r < 2 && r < first_row) continue;                       // still in LDS from the previous strip
+        if (r < 2 && r < first_row) continue;                       // already in LDS (or known to be zero there)
         const int gy = y0 - 1 + r;                                  // same for the whole workgroup
         const bool rowok = gy >= 0 && gy < h;
-        const int rslot = rot + r >= kRows + 2 ? rot + r - (kRows + 2) : rot + r;
         const uint32_t rowoff = img_off + (uint32_t)(gy * w * C * 2);
+        const int rslot = (ring_pos + r) % nslot;
 #pragma unroll
         for (int qi = 0; qi < K::QPW; ++qi) {
             const int q = wave + 4 * qi;                            // same for the whole wavefront
             if (4 * qi + 3 < K::PIECES || q < K::PIECES) {
-                {
-                    const uint32_t off = (rowok && coff[qi] < kSlotZero) ? rowoff + coff[qi] : 0u;
-                    __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + rslot * K::ROWB + q * 1024), 16, 0,
-                                                     0);
-                }
+                const uint32_t off = (rowok && coff[qi] != kSlotZero) ? rowoff + coff[qi] : 0u;
+                __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + rslot * K::ROWB + q * 1024), 16, 0, 0);
             }
         }
+        __builtin_amdgcn_sched_barrier(0); // one row's addresses at a time
     }
-}
-
-// the strip buffer starts as zeros (see issue_strip_loads)
-template <int C>
-__device__ __forceinline__ void zero_strip_buffer(uint8_t *lds, int tid)
-{
-    typedef MidCfg<C> K;
-    for (int i = tid * 16; i < K::LDS_BYTES; i += 256 * 16) *(u32x4 *)(lds + i) = (u32x4){0u, 0u, 0u, 0u};
 }
 
 // Accumulates RW output rows of one 32-pixel x 32-channel block from the staged strip.
@@ -186,10 +178,13 @@ __device__ __forceinline__ void zero_strip_buffer(uint8_t *lds, int tid)
 // `rowp` holds the LDS byte address of each staged row for this lane.
 // POOL: all rows are summed into acc[0] / acc[1] (global average pool of the last layer); rows at or
 // beyond `rows_valid` are skipped (RAGGED: the last strip of a tile whose height is not a multiple of kRows).
-template <int C, int RW, bool POOL, bool RAGGED = false>
+// INIT: the accumulators are not read; the first matrix instruction of every output row starts from zero.
+template <int C, int RW, bool POOL, bool RAGGED = false, bool INIT = false>
 __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf16x8 (&Wr)[9][C / 16],
                                           f32x16 *acc, int rows_valid)
 {
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    bool started[RW] = {};
     typedef MidCfg<C> K;
     constexpr int NP = (RW + 2) / 2;  // row pairs
     constexpr int KP = K::KC / 2;     // pairs of k chunks
@@ -221,6 +216,9 @@ __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf
                 if (orow >= 0 && orow < RW) {
                     if (POOL) {
                         if (!RAGGED || orow < rows_valid) acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow & 1]);
+                    } else if (INIT && !started[orow]) {
+                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[j], zero);
+                        started[orow] = true;
                     } else {
                         acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow]);
                     }
@@ -292,10 +290,19 @@ __device__ __forceinline__ void lds_accumulate(float *slot16, const float (&tv)[
     }
 }
 
+__device__ __forceinline__ void lds_accumulate4(float *slot4, const float (&tv)[4], bool pred)
+{
+    if (pred) {
+        f32x4 cur = *(f32x4 *)slot4;
+        cur[0] += tv[0]; cur[1] += tv[1]; cur[2] += tv[2]; cur[3] += tv[3];
+        *(f32x4 *)slot4 = cur;
+    }
+}
+
 struct StatArgs {
     const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
     int in_slots;
-    const float *rsum;  // [C][C] residual-weight sums of this layer (fp32), or nullptr
+    const float *rsum;  // [c_in][c_out] residual-weight sums of this layer (fp32), or nullptr
     float *tout;        // records written by this launch [n_img][out_slots][stat_rec(C,NQ)], or nullptr
     int out_slots;
     int per;            // tiles per workgroup: divides, or is a multiple of, the tiles of one image
@@ -304,32 +311,57 @@ struct StatArgs {
 constexpr int MODE_MID = 0;  // write activations, sample channel sums from every eighth strip
 constexpr int MODE_LAST = 1; // last block: no activations, the nine border-aware channel sums
 
-// C -> C (+bias, ReLU), bf16 NHWC in / out.  Two workgroups per CU: while one waits for its strip to
-// land in LDS the other keeps the matrix cores busy.
+constexpr int kMidWaves = 8; // wavefronts of a conv_mid workgroup: two groups of four
+
 template <int C, int MODE>
-__global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
-                                                          ConvGeom g, const bf16_t *__restrict__ wfrag,
-                                                          const float *__restrict__ bias, StatArgs st,
-                                                          bf16_t *__restrict__ out)
+struct MidRing {
+    static constexpr int NQ = MODE == MODE_LAST ? 9 : 1;      // sums per channel in a statistics record
+    static constexpr int NSLOT = MODE == MODE_LAST ? 14 : 15; // row slots of the LDS ring (>= 12)
+    static constexpr int NSUB = kMidWaves / MidCfg<C>::NCB;   // statistics records a workgroup writes per image
+};
+
+// C -> C (+bias, ReLU), bf16 NHWC in / out.  One persistent workgroup of eight wavefronts per CU, two
+// wavefronts per SIMD.  The workgroup walks down its run of strips; the two groups of four wavefronts
+// take alternate strips and work in opposite phases: in phase p group (p & 1) runs the matrix
+// instructions of strip p while the other group adds the bias to, converts and stores strip p-1 and
+// issues the direct-to-LDS loads of strip p+2.  One workgroup barrier ends a phase.  The matrix cores thus always have one wavefront per SIMD feeding them while the other
+// does the vector / memory work, and every load has a whole phase to land before anyone waits for it.
+//
+// Staged rows live in a ring of NSLOT row slots.  Rows are loaded in the order the run needs them, so
+// ring position = number of rows loaded before: strip i of the run loads nr(i) new rows at positions
+// base(i).. and reads the six rows from wstart(i):
+//   i = 0                      : 6 rows,             wstart = base
+//   strip below the previous   : 4 rows (two rows are shared with the strip above), wstart = base - 2
+//   first strip of a new image : 5 rows (the row above the tile is zero - and so is the last row the
+//                                previous strip loaded, which lay below its tile), wstart = base - 1
+template <int C, int MODE>
+__global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
+                                                                     ConvGeom g, const bf16_t *__restrict__ wfrag,
+                                                                     const float *__restrict__ bias, StatArgs st,
+                                                                     bf16_t *__restrict__ out)
 {
     typedef MidCfg<C> K;
-    constexpr int RG = 2 / K::NCB;     // row groups among the 4 wavefronts
+    typedef MidRing<C, MODE> R;
+    constexpr int RG = 2 / K::NCB;     // row groups among the 4 wavefronts of a group
     constexpr int RW = kRows / RG;     // output rows per wavefront
-    constexpr int NQ = MODE == MODE_LAST ? 9 : 1;
-    constexpr int PARTS = 256 / C;
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[K::LDS_BYTES];
-    __shared__ __attribute__((aligned(16))) float s_stat[4][NQ][32]; // per wavefront, 32 channels of its block
-    __shared__ __attribute__((aligned(16))) float s_init[C];         // bias + rounding-residual correction
-    __shared__ float s_mean[C];
-    __shared__ float s_red[PARTS][C];
-    __shared__ float s_cnt[4];
+    constexpr int NQ = R::NQ, NSLOT = R::NSLOT;
+    constexpr int WIN = kRows + 2;     // staged rows one strip reads
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[NSLOT * K::ROWB];
+    __shared__ __attribute__((aligned(16))) float s_stat[kMidWaves][NQ][32]; // per wavefront, 32 channels of its block
+    // bias + rounding-residual correction per image, indexed by image mod 4: it is written two phases
+    // before the image's first strip is multiplied and read until one phase after its last, and an
+    // image may be a single strip
+    __shared__ __attribute__((aligned(16))) float s_init[4][C];
+    __shared__ __attribute__((aligned(16))) float s_mean[kMidWaves][C];
+    __shared__ float s_cnt[kMidWaves];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, w4 = wave & 3;
     const int px = lane & 31, half = lane >> 5;
-    const int cb = wave % K::NCB;
-    const int xb = (wave / K::NCB) & 1;
-    const int rg = wave / (K::NCB * 2);
+    const int cb = w4 % K::NCB;
+    const int xb = (w4 / K::NCB) & 1;
+    const int rg = w4 / (K::NCB * 2);
 
     bf16x8 Wr[9][K::KC];
     load_weight_frags<C>(Wr, wfrag, cb, lane);
@@ -338,210 +370,245 @@ __global__ __launch_bounds__(256, 2) void conv_mid_kernel(const uint8_t *__restr
     const int total = g.n_img * tpi;
     const int vb = xcd_virtual_block(blockIdx.x, gridDim.x);
     const int t_begin = vb * st.per;
-    const int t_end = min(total, t_begin + st.per);
+    const int ns = min(total, t_begin + st.per) - t_begin; // strips of this workgroup's run
+    if (ns <= 0) return;
     const int out_slot = st.per >= tpi ? 0 : (t_begin % tpi) / st.per;
-    const uint8_t *lbase = lds + (xb * 32 + px) * K::PS + half * 16;
-    float *my_stat = &s_stat[wave][0][half * 16];
+    const lrow_t lbase = lds_address(lds) + (xb * 32 + px) * K::PS + half * 16;
+    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
 
-    // tile order: image, column block, strip - consecutive tiles of a workgroup are vertically adjacent
-    // strips, which share two staged rows
-    auto decode = [&](int t, int &n, int &strip, int &x0) {
-        strip = t % g.strips;
-        const int colblk = (t / g.strips) % g.colblks;
-        n = t / tpi;
-        x0 = colblk * kTileW;
+    // ---- geometry of the strips of the run (tile order: image, column block, strip), kept as counters
+    // that are advanced once per phase; all wave-uniform
+    struct Geo {
+        int i;      // index in the run
+        int strip;  // strip within its column of the tile
+        int colblk; // column block within the image
+        int n;      // image
+        int base;   // ring position of its first new row
     };
-    // The kRows + 2 row slots of the strip buffer form a ring: window row j of strip s (image row
-    // s*kRows - 1 + j) lives in slot (s*kRows + j) mod (kRows + 2), so the last two rows of a strip are
-    // already in place as the first two rows of the strip below it and only kRows rows are loaded.
-    auto ring_rot = [](int strip) { return (strip * kRows) % (kRows + 2); };
-    auto zero_stats = [&]() {
-        for (int i = tid; i < 4 * NQ * 32; i += 256) (&s_stat[0][0][0])[i] = 0.f;
-        if (tid < 4) s_cnt[tid] = 0.f;
-    };
-    // writes the record of image n and clears the accumulators
-    auto flush = [&](int n) {
-        __syncthreads();
-        float *rec = st.tout + ((int64_t)n * st.out_slots + out_slot) * stat_rec(C, NQ);
-        for (int i = tid; i < NQ * C; i += 256) {
-            const int q = i / C, o = i - q * C;
-            float v = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-                if (w % K::NCB == o / 32) v += s_stat[w][q][o & 31];
-            rec[i] = v;
+    auto rows_loaded = [&](const Geo &q) { return q.i == 0 ? WIN : (q.strip == 0 ? WIN - 1 : kRows); };
+    auto first_row = [&](const Geo &q) { return WIN - rows_loaded(q); }; // first window row that is loaded
+    auto wstart = [&](const Geo &q) { return q.base - first_row(q); };
+    auto advance = [&](Geo &q) {
+        q.base += rows_loaded(q);
+        ++q.i;
+        if (++q.strip == g.strips) {
+            q.strip = 0;
+            if (++q.colblk == g.colblks) {
+                q.colblk = 0;
+                ++q.n;
+            }
         }
-        if (tid == 0) rec[NQ * C] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-        __syncthreads();
-        zero_stats();
-        __syncthreads();
     };
-    // s_init[o] = bias[o] + sum_c rsum[o][c] * mean_n[c]
+    Geo gc{0, t_begin % g.strips, (t_begin / g.strips) % g.colblks, t_begin / tpi, 0}; // strip p
+    Geo g1 = gc;                                                                          // strip p + 1
+    advance(g1);
+    Geo g2 = g1;                                                                          // strip p + 2
+    advance(g2);
+    Geo gp = gc;                                                                          // strip p - 1 (from phase 1 on)
+
+    auto issue = [&](const Geo &q) {
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)q.n * img_bytes, g.h, g.w, q.strip * kRows, q.colblk * kTileW, w4,
+                             pin_in_loop(lane), first_row(q), wstart(q), NSLOT);
+    };
+    // s_init[n & 3][o] = bias[o] + sum_c rsum[c][o] * mean_n[c], by the four wavefronts of one group:
+    // each takes C/4 outputs, its lanes split the sum over c in 64 / (C/4) parts
     auto prepare_init = [&](int n) {
-        __syncthreads();
-        if (st.tin && st.rsum) {
-            if (tid < C) {
+        constexpr int OPW = C / 4, PARTS = 64 / OPW, CP = C / PARTS;
+        const int lane = pin_in_loop(tid & 63);
+        const int o = w4 * OPW + lane % OPW, part = lane / OPW;
+        float d = 0.f;
+        const float *tin = st.tin, *rsum = st.rsum;
+        if (tin && rsum) {
+            if (lane < C) {
                 float sum = 0.f, cnt = 0.f;
                 for (int s2 = 0; s2 < st.in_slots; ++s2) {
-                    const float *rec = st.tin + ((int64_t)n * st.in_slots + s2) * stat_rec(C, 1);
-                    sum += rec[tid];
+                    const float *rec = tin + ((int64_t)n * st.in_slots + s2) * stat_rec(C, 1);
+                    sum += rec[lane];
                     cnt += rec[C];
                 }
-                s_mean[tid] = cnt > 0.f ? sum / cnt : 0.f;
+                s_mean[wave][lane] = cnt > 0.f ? sum / cnt : 0.f;
             }
-            __syncthreads();
-            {
-                const int o = tid % C, part = tid / C;
-                float d = 0.f;
-                for (int c = part * (C / PARTS); c < (part + 1) * (C / PARTS); ++c) d = fmaf(st.rsum[o * C + c], s_mean[c], d);
-                s_red[part][o] = d;
+#pragma unroll 4
+            for (int k = 0; k < CP; ++k) { // (little unrolling: registers are scarce here)
+                const int c = part * CP + k;
+                d = fmaf(rsum[c * C + o], s_mean[wave][c], d);
             }
-            __syncthreads();
-            if (tid < C) {
-                float v = bias[tid];
 #pragma unroll
-                for (int p2 = 0; p2 < PARTS; ++p2) v += s_red[p2][tid];
-                s_init[tid] = v;
-            }
-        } else if (tid < C) {
-            s_init[tid] = bias[tid];
+            for (int sh = OPW; sh < 64; sh <<= 1) d += __shfl_xor(d, sh);
         }
-        // leave nothing in flight: the strip loop counts outstanding vector-memory operations
-        __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        __syncthreads();
+        if (part == 0) s_init[n & 3][o] = bias[o] + d;
     };
-
-    const int sample_phase = min(3, g.strips - 1); // strips 3, 11, 19, .. are sampled (the last one of a short tile)
-    const bool prezero = g.colblks == 1;
-    zero_strip_buffer<C>(lds, tid);
-    zero_stats();
-    __syncthreads();
-    if (t_begin < t_end) {
-        int n, strip, x0;
-        decode(t_begin, n, strip, x0);
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * (uint32_t)(g.h * g.w * C * 2), g.h, g.w, strip * kRows, x0,
-                             prezero, wave, lane, 0, ring_rot(strip));
-    }
-    __builtin_amdgcn_s_waitcnt(kWaitVm0); // weights (and the first strip) are in
-    int cur_n = -1;
-    bool stores_behind_loads = false;
-    for (int t = t_begin; t < t_end; ++t) {
-        int n, strip, x0;
-        decode(t, n, strip, x0);
-        const int y0 = strip * kRows;
-        if (n != cur_n) { // same for the whole workgroup
-            if (cur_n >= 0 && st.tout) flush(cur_n);
-            prepare_init(n);
-            cur_n = n;
-        }
-
-        // accumulators start from bias + correction (16 consecutive channels per lane)
-        f32x16 acc[RW];
+    // this wavefront's statistics of image n -> its record; accumulators cleared
+    auto flush = [&](int n) {
+        if (st.tout) {
+            const int lane = pin_in_loop(tid & 63);
+            float *rec = st.tout + (((int64_t)n * st.out_slots + out_slot) * R::NSUB + wave / K::NCB) * stat_rec(C, NQ);
+            if (lane < 32) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const f32x4 bq = *(const f32x4 *)(&s_init[cb * 32 + half * 16 + 4 * q]);
-#pragma unroll
-            for (int r = 0; r < RW; ++r) {
-                acc[r][4 * q] = bq[0]; acc[r][4 * q + 1] = bq[1]; acc[r][4 * q + 2] = bq[2]; acc[r][4 * q + 3] = bq[3];
+                for (int q = 0; q < NQ; ++q) {
+                    rec[q * C + cb * 32 + lane] = s_stat[wave][q][lane];
+                    s_stat[wave][q][lane] = 0.f;
+                }
+            }
+            if (cb == 0 && lane == 0) {
+                rec[NQ * C] = s_cnt[wave];
+                s_cnt[wave] = 0.f;
             }
         }
-
-        // Vector memory operations complete in issue order.  After a full strip every wavefront has issued
-        // its 2 * RW activation stores behind the loads of the next strip: waiting until at most that many
-        // operations are outstanding means the loads have landed, without waiting for the stores.
-        if (stores_behind_loads) __builtin_amdgcn_s_waitcnt(kWaitVm0 | (2 * RW));
-        else __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        lds_barrier(); // the strip has landed for every wavefront
-        {
-            lrow_t rowp[RW + 2];
-            const int start = ring_rot(strip) + rg * RW;
-#pragma unroll
-            for (int r = 0; r < RW + 2; ++r) rowp[r] = lds_address(lbase) + ((start + r) % (kRows + 2)) * K::ROWB;
-            strip_mma<C, RW, false>(rowp, Wr, acc, RW);
-        }
-        lds_barrier(); // everyone is done reading: the rows no longer needed may be overwritten
-        if (t + 1 < t_end) {
-            int n2, strip2, x2;
-            decode(t + 1, n2, strip2, x2);
-            const bool below = n2 == n && x2 == x0 && strip2 == strip + 1;
-            issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n2 * (uint32_t)(g.h * g.w * C * 2), g.h, g.w,
-                                 strip2 * kRows, x2, prezero, wave, lane, below ? 2 : 0, ring_rot(strip2));
-        }
-
+    };
+    f32x16 acc[RW];
+    const int sample_phase = min(3, g.strips - 1); // strips 3, 11, 19, .. are sampled (the last one of a short tile)
+    // bias, ReLU, bf16, stores and statistics of strip i (accumulated by this wavefront)
+    auto epilogue = [&](const Geo &q) {
+        const int lane = pin_in_loop(tid & 63);
+        const int px = lane & 31, half = lane >> 5;
+        float *my_stat = &s_stat[wave][0][half * 16];
+        const int strip = q.strip, n = q.n, x0 = q.colblk * kTileW;
+        const int y0 = strip * kRows;
         const int x = x0 + xb * 32 + px;
         const int yw = y0 + rg * RW; // first output row of this wavefront
+        // The sums start from zero: bias + correction of the image (s_init, 16 channels per lane) is added
+        // on the way out, never in place - the accumulators stay untouched, so that no second copy of them
+        // is ever alive next to the weights.
+        const float *si = &s_init[n & 3][cb * 32 + half * 16];
         if (MODE == MODE_MID) {
             // element offset of this lane's first row; the activation buffer is below 2^31 elements
             const uint32_t e0 = (uint32_t)(((n * g.h + yw) * g.w + x) * C + cb * 32 + half * 16);
             const bool full = y0 + kRows <= g.h && x0 + kTileW <= g.w; // same for the whole workgroup
-            if (full) {
 #pragma unroll
-                for (int r = 0; r < RW; ++r) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
-            } else {
+            for (int hq = 0; hq < 2; ++hq) { // 8 channels = one 16-byte store per row
+                const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                 for (int r = 0; r < RW; ++r) {
-                    if (yw + r < g.h && x < g.w) store_tile_bf16(out + (e0 + (uint32_t)(r * g.w * C)), acc[r], true);
+                    u32x4 pk;
+                    pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
+                    pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
+                    pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
+                    pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                    bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                    if (full) *(u32x4 *)dst = pk;
+                    else if (yw + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                    __builtin_amdgcn_sched_barrier(0); // one store at a time keeps the temporaries few
                 }
             }
-            stores_behind_loads = full;
         }
         if (st.tout && (MODE == MODE_LAST || (strip & 7) == sample_phase)) {
-            // per-lane sum over this wavefront's valid rows of relu(output)
-            float tv[16];
+            // four channels at a time (registers are scarce next to weights and accumulators)
+            const bool colok = x < g.w;
+            const int rl = g.h - 1 - yw; // image row h-1 relative to this wavefront's rows
 #pragma unroll
-            for (int v = 0; v < 16; ++v) tv[v] = 0.f;
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 bq = *(const f32x4 *)(si + 4 * q);
+                float tv[4] = {0.f, 0.f, 0.f, 0.f}; // sum over this wavefront's valid rows of relu(output)
 #pragma unroll
-            for (int r = 0; r < RW; ++r)
-                if (yw + r < g.h) {
+                for (int r = 0; r < RW; ++r)
+                    if (yw + r < g.h) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) tv[v] += fmaxf(acc[r][v], 0.f);
+                        for (int e = 0; e < 4; ++e) tv[e] += fmaxf(acc[r][4 * q + e] + bq[e], 0.f);
+                    }
+                if (!colok) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) tv[e] = 0.f;
                 }
-            if (x >= g.w) {
+                if (MODE == MODE_LAST) {
+                    lds_accumulate4(my_stat + 3 * 32 + 4 * q, tv, x == 0);         // first column
+                    lds_accumulate4(my_stat + 4 * 32 + 4 * q, tv, x == g.w - 1);   // last column
+                }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) tv[v] = 0.f;
-            }
-            if (MODE == MODE_LAST) {
-                lds_accumulate(my_stat + 3 * 32, tv, x == 0);         // first column
-                lds_accumulate(my_stat + 4 * 32, tv, x == g.w - 1);   // last column
-            }
+                for (int e = 0; e < 4; ++e) tv[e] = half_sum(tv[e]);
+                lds_accumulate4(my_stat + 4 * q, tv, px == kSumLane);              // whole tile (or its sampled strips)
+                if (MODE == MODE_LAST) {
+                    if (yw == 0) { // image row 0 is this wavefront's first row
+                        float rv[4];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) tv[v] = half_sum(tv[v]);
-            lds_accumulate(my_stat, tv, px == kSumLane);                    // whole tile (or its sampled strips)
+                        for (int e = 0; e < 4; ++e) rv[e] = colok ? fmaxf(acc[0][4 * q + e] + bq[e], 0.f) : 0.f;
+                        lds_accumulate4(my_stat + 5 * 32 + 4 * q, rv, x == 0);
+                        lds_accumulate4(my_stat + 6 * 32 + 4 * q, rv, x == g.w - 1);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
+                        lds_accumulate4(my_stat + 1 * 32 + 4 * q, rv, px == kSumLane);
+                    }
+                    if (rl >= 0 && rl < RW) {
+                        float rv[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            float a = acc[0][4 * q + e];
+#pragma unroll
+                            for (int r = 1; r < RW; ++r) a = rl == r ? acc[r][4 * q + e] : a;
+                            rv[e] = colok ? fmaxf(a + bq[e], 0.f) : 0.f;
+                        }
+                        lds_accumulate4(my_stat + 7 * 32 + 4 * q, rv, x == 0);
+                        lds_accumulate4(my_stat + 8 * 32 + 4 * q, rv, x == g.w - 1);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
+                        lds_accumulate4(my_stat + 2 * 32 + 4 * q, rv, px == kSumLane);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (cb == 0 && lane == 0) {
                 const int rows = max(0, min(RW, g.h - yw)), cols = max(0, min(32, g.w - (x0 + xb * 32)));
                 s_cnt[wave] += (float)(rows * cols);
             }
-            if (MODE == MODE_LAST) {
-                if (yw == 0) { // image row 0 is this wavefront's first row
-                    float rv[16];
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) rv[v] = x < g.w ? fmaxf(acc[0][v], 0.f) : 0.f;
-                    lds_accumulate(my_stat + 5 * 32, rv, x == 0);
-                    lds_accumulate(my_stat + 6 * 32, rv, x == g.w - 1);
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
-                    lds_accumulate(my_stat + 1 * 32, rv, px == kSumLane);
-                }
-                const int rl = g.h - 1 - yw; // image row h-1 relative to this wavefront's rows
-                if (rl >= 0 && rl < RW) {
-                    float rv[16];
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float a = acc[0][v];
-#pragma unroll
-                        for (int r = 1; r < RW; ++r) a = rl == r ? acc[r][v] : a;
-                        rv[v] = x < g.w ? fmaxf(a, 0.f) : 0.f;
-                    }
-                    lds_accumulate(my_stat + 7 * 32, rv, x == 0);
-                    lds_accumulate(my_stat + 8 * 32, rv, x == g.w - 1);
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) rv[v] = half_sum(rv[v]);
-                    lds_accumulate(my_stat + 2 * 32, rv, px == kSumLane);
-                }
-            }
         }
+    };
+
+    // ---- prologue: statistics cleared, corrections of the first image(s), strips 0 and 1 on their way
+    if (lane < 32) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) s_stat[wave][q][lane] = 0.f;
     }
-    if (cur_n >= 0 && st.tout) flush(cur_n);
+    if (lane == 0) s_cnt[wave] = 0.f;
+    if (grp == 0) prepare_init(gc.n);
+    else if (ns > 1 && g1.n != gc.n) prepare_init(g1.n);
+    if (grp == 1) {
+        issue(gc);
+        if (ns > 1) issue(g1);
+    }
+    int issued_upto = min(1, ns - 1);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0); // weights, and for the loading group strips 0 and 1, are in
+    lds_barrier();
+
+    for (int p = 0; p <= ns; ++p) {
+        const bool mma_phase = (p & 1) == grp;
+        if (mma_phase) {
+            if (p < ns) {
+                lrow_t rowp[RW + 2];
+                const int start = wstart(gc) + rg * RW;
+#pragma unroll
+                for (int r = 0; r < RW + 2; ++r) rowp[r] = lbase + (uint32_t)((start + r) % NSLOT) * K::ROWB;
+                __builtin_amdgcn_s_setprio(3); // the matrix stream goes first whenever both wavefronts of a SIMD are ready
+                strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                __builtin_amdgcn_s_setprio(0);
+            }
+        } else {
+            if (p >= 1) epilogue(gp);
+        }
+        // Loads: the group that is not multiplying issues strips p + 1 (only if it did not fit earlier) and
+        // p + 2, as far as the ring has room (strip p is being read: everything from wstart(p) on is
+        // live; strip p + 1 always fits).  Every wavefront keeps the count.
+        bool late = false;
+        if (issued_upto == p && p + 1 < ns) {
+            if (!mma_phase) {
+                issue(g1);
+                late = true; // this group reads it in the very next phase
+            }
+            issued_upto = p + 1;
+        }
+        if (issued_upto == p + 1 && p + 2 < ns && g2.base + rows_loaded(g2) - wstart(gc) <= NSLOT) {
+            if (!mma_phase) issue(g2);
+            issued_upto = p + 2;
+        }
+        if (!mma_phase && p + 2 < ns && g2.n != g1.n) prepare_init(g2.n);
+        if (p >= 1 && (p == ns || gc.n != gp.n)) flush(gp.n); // strip p - 1 was the last of its image in this run
+        // what this group issued a phase ago (or, late, just now) must have landed before the barrier
+        if (mma_phase || late) __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        lds_barrier();
+        gp = gc;
+        gc = g1;
+        g1 = g2;
+        advance(g2);
+    }
 }
 
 // Final conv C -> 64 output channels per grid.y slice, summed over the pixels of one (image, column
@@ -580,8 +647,6 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
 #pragma unroll
     for (int r = 0; r < RW + 2; ++r) rowp[r] = lds_address(lds) + r * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
     const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
-    const bool prezero = g.colblks == 1;
-    zero_strip_buffer<C>(lds, tid);
 
     for (int t = t_begin; t < t_end; ++t) {
         const int colblk = t % g.colblks;
@@ -594,7 +659,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
         for (int v = 0; v < 16; ++v) { sum[0][v] = 0.f; sum[1][v] = 0.f; }
 
         __syncthreads();
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, prezero, wave, lane);
+        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, wave, lane);
         for (int strip = 0; strip < g.strips; ++strip) {
             const int y0 = strip * kRows;
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -604,8 +669,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
                 else strip_mma<C, RW, true, true>(rowp, Wr, sum, g.h - y0);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, prezero,
-                                         wave, lane);
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
             } else {
                 f32x16 acc[RW];
 #pragma unroll
@@ -615,8 +679,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
                 strip_mma<C, RW, false>(rowp, Wr, acc, RW);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, prezero,
-                                         wave, lane);
+                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
                     if (y0 + r < g.h)
@@ -982,7 +1045,7 @@ hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g
                            const Partition &part, bool last, bf16_t *out, hipStream_t s)
 {
     StatArgs st{tin, in_slots, rsum, tout, part.slots, part.per};
-    const dim3 grid(part.blocks), block(256);
+    const dim3 grid(part.blocks), block(64 * kMidWaves);
     if (C == 64) {
         if (last) hipLaunchKernelGGL((conv_mid_kernel<64, MODE_LAST>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
         else hipLaunchKernelGGL((conv_mid_kernel<64, MODE_MID>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
@@ -1007,9 +1070,10 @@ hipError_t launch_head(const float *recs, int slots, int C, int64_t n_img, int n
 // Tiles are dealt to workgroups in contiguous runs of `per`; `per` divides the tiles of one image or is
 // a multiple of them, so a workgroup never holds two partial images and an image is touched by exactly
 // `slots` workgroups.
-Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks)
+Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks, int sub)
 {
     Partition p{};
+    p.sub = sub;
     const int64_t total = n_img * tiles_per_image;
     int64_t want = (total + target_blocks - 1) / target_blocks;
     if (want < 1) want = 1;
@@ -1027,6 +1091,8 @@ Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks)
 }
 
 size_t stat_record_floats(int C, int nq) { return (size_t)stat_rec(C, nq); }
+
+int conv_mid_records_per_workgroup(int C) { return kMidWaves / (C / 32); }
 
 hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
                              const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,

@@ -8,6 +8,7 @@
 #include <string>
 #include <vector>
 
+#include <stdlib.h>
 #include "qrm_internal.h"
 
 using namespace qrm;
@@ -136,10 +137,11 @@ void pack_first(const float *w, const float *scale, int cout, std::vector<uint16
 
 // rsum[o][c] = sum over the 9 taps of (w*scale - bf16(w*scale)): what the bf16 weights leave out, as it
 // acts on a spatially constant input
+// appended as [c_in][c_out]: the lanes of the kernel that applies it run over c_out
 void residual_sums(const float *w, const float *scale, int C, std::vector<float> &dst)
 {
-    for (int o = 0; o < C; ++o)
-        for (int ci = 0; ci < C; ++ci) {
+    for (int ci = 0; ci < C; ++ci)
+        for (int o = 0; o < C; ++o) {
             double r = 0.0;
             for (int tap = 0; tap < 9; ++tap) {
                 const float v = w[((size_t)o * C + ci) * 9 + tap] * (scale ? scale[o] : 1.f);
@@ -176,7 +178,7 @@ struct WsLayout {
 
 int tiles_per_image(int h, int w) { return ((h + kRows - 1) / kRows) * ((w + kTileW - 1) / kTileW); }
 int first_blocks(const qrm_ctx *c) { return 8 * c->num_cu; }
-int mid_blocks(const qrm_ctx *c) { return 2 * c->num_cu; }
+int mid_blocks(const qrm_ctx *c) { return c->num_cu; } // one persistent workgroup per CU
 
 WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
 {
@@ -192,8 +194,10 @@ WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
         const int64_t counts[2] = {L.mb, N % L.mb};
         for (int64_t cnt : counts) {
             if (cnt <= 0) continue;
-            const Partition pf = make_partition(cnt, tpi, first_blocks(c)), pm = make_partition(cnt, tpi, mid_blocks(c));
-            const size_t r = (size_t)cnt * (pf.slots > pm.slots ? pf.slots : pm.slots);
+            const Partition pf = make_partition(cnt, tpi, first_blocks(c));
+            const Partition pm = make_partition(cnt, tpi, mid_blocks(c), conv_mid_records_per_workgroup(c->C));
+            const int rf = pf.slots * pf.sub, rm = pm.slots * pm.sub;
+            const size_t r = (size_t)cnt * (rf > rm ? rf : rm);
             if (r > recs) recs = r;
         }
         L.stats = align_up(recs * stat_record_floats(c->C, 9) * 4);
@@ -228,9 +232,17 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
             return fail(c, QRM_E_NOMEM, buf);
         }
         slot->bytes = bytes;
-        // the block of zeros the convolutions read their padding from; written once per allocation
-        e = hipMemset(slot->ws, 0, kZeroBytes);
-        if (e != hipSuccess) return hip_fail(c, e, "hipMemset(workspace zero block)");
+        // Debugging aid: QRM_POISON_WORKSPACE=1 fills a new workspace with 0xFF bytes (NaN as bf16 / fp32),
+        // so that a kernel reading something no kernel wrote shows up in the results.
+        static const bool poison = getenv("QRM_POISON_WORKSPACE") != nullptr;
+        if (poison) {
+            e = hipMemsetAsync(slot->ws, 0xFF, bytes, s);
+            if (e != hipSuccess) return hip_fail(c, e, "hipMemsetAsync(workspace poison)");
+        }
+        // The block of zeros the convolutions read their padding from; written once per allocation, on
+        // the stream of the kernels that read it (the stream may not synchronise with the null stream).
+        e = hipMemsetAsync(slot->ws, 0, kZeroBytes, s);
+        if (e != hipSuccess) return hip_fail(c, e, "hipMemsetAsync(workspace zero block)");
     }
     *out = slot;
     return QRM_OK;
@@ -256,10 +268,11 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
     for (int64_t n0 = 0; n0 < N; n0 += L.mb) {
         const int cnt = (int)((N - n0 < L.mb) ? (N - n0) : L.mb);
         ConvGeom g{cnt, h, w, (h + kRows - 1) / kRows, (w + kTileW - 1) / kTileW};
-        const Partition pf = make_partition(cnt, tpi, first_blocks(c)), pm = make_partition(cnt, tpi, mid_blocks(c));
+        const Partition pf = make_partition(cnt, tpi, first_blocks(c));
+        const Partition pm = make_partition(cnt, tpi, mid_blocks(c), conv_mid_records_per_workgroup(c->C));
         src.img = img0 + n0 * 3 * (int64_t)src.H * src.W;
         src.off = off0 ? off0 + 2 * n0 : nullptr;
-        int cur = 0, tcur = 0, in_slots = pf.slots;
+        int cur = 0, tcur = 0, in_slots = pf.slots * pf.sub;
         e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
         if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
         const int blocks = n_run > 0 ? n_run : c->n_blocks;
@@ -290,7 +303,7 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
             }
             cur ^= 1;
             tcur ^= 1;
-            in_slots = pm.slots;
+            in_slots = pm.slots * pm.sub;
         }
         if (n_run > 0) {
             e = launch_nhwc_to_nchw(buf[cur], cnt, h, w, c->C, d_act + n0 * (int64_t)c->C * h * w, s);

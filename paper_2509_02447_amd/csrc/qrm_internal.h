@@ -44,10 +44,12 @@ hipError_t launch_extract_tiles(const uint8_t *img, int64_t N, int H, int W, con
 // How the tiles of a launch are dealt to workgroups (see make_partition).
 struct Partition {
     int per;    // tiles per workgroup
-    int slots;  // workgroups that touch one image = statistics records per image
+    int slots;  // workgroups that touch one image
+    int sub;    // statistics records a workgroup writes per image; records per image = slots * sub
     int blocks; // grid size
 };
-Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks);
+Partition make_partition(int64_t n_img, int tiles_per_image, int target_blocks, int sub = 1);
+int conv_mid_records_per_workgroup(int C);
 size_t stat_record_floats(int C, int nq); // floats per statistics record holding nq sums per channel
 
 // conv1: crop + normalise + conv3x3 (3 -> C, bf16 high + residual weights) + bias + ReLU -> bf16 NHWC;
@@ -57,7 +59,8 @@ hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const
 
 // conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out.  The input is addressed as ws + in_off (+ 32-bit
 // offsets); the first kZeroBytes of ws must be zero: they are the source of the zero padding.
-// tin / in_slots / rsum: channel sums of the input and the summed weight-rounding residual [C][C] used
+// tin / in_slots / rsum: channel sums of the input (in_slots records per image) and the summed weight-rounding
+// residual [c_in][c_out] used
 // to correct the bias (either may be null).  tout: statistics of the output.  last: no activations are
 // written, tout receives the nine border-aware sums per channel (stat_record_floats(C,9) per record).
 constexpr size_t kZeroBytes = 256;
