@@ -174,6 +174,28 @@ QRM_API qrm_status qrm_detect(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, 
                       uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
 
 /*
+ * The same path for a batch that lives in HOST memory, streamed through the GPU in chunks (the
+ * pipelined detection of Section 5: the transfer of one mini-batch overlaps the kernels of another;
+ * Section 7 streams up to a million images this way).  The context owns three (default-priority)
+ * streams, one per role: uploads follow each other back to back on the first, the kernels of a chunk
+ * run on the second once its upload is done, its results go home on the third.  `depth` (1..
+ * QRM_MAX_STREAMS) is the number of chunks in flight = staging buffers on the device
+ * (depth * chunk_images * 3*H*W bytes): 1 serialises, 2 overlaps upload and kernels, 3 adds slack.
+ * h_chunks: n_chunks HOST pointers, each to u8 [chunk_images,3,H,W]; the same buffer may appear more
+ * than once (a caller that refills a few buffers round-robin).  For copies that overlap with kernels
+ * the buffers must be page-locked (hipHostMalloc); pageable memory works but serialises.
+ * h_off_chunks: n_chunks HOST pointers to i32 [chunk_images,2], or NULL (= origin 0,0 everywhere).
+ * h_msg u8 [n_chunks*chunk_images,k]; h_codeword u8 [n_chunks*chunk_images,n] or NULL;
+ * h_nerr i8 [n_chunks*chunk_images]: HOST buffers, chunk after chunk.
+ * The call returns when every chunk is done.  Errors: as qrm_detect, plus QRM_E_INVALID for depth
+ * outside 1..QRM_MAX_STREAMS, chunk_images <= 0, n_chunks < 0 or a NULL chunk pointer.
+ */
+QRM_API qrm_status qrm_detect_host(qrm_ctx *ctx, const uint8_t *const *h_chunks, int32_t n_chunks,
+                                   int32_t chunk_images, int32_t H, int32_t W,
+                                   const int32_t *const *h_off_chunks, int32_t tile, int32_t depth,
+                                   uint8_t *h_msg, uint8_t *h_codeword, int8_t *h_nerr);
+
+/*
  * Per-launch timing of the dominant kernel (the C -> C convolution), for benchmarks: while enabled,
  * every launch of that kernel is bracketed by two hipEvents recorded on the stream it is launched on.
  * qrm_profile_read waits for the recorded events, returns the summed duration in milliseconds, the

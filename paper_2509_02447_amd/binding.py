@@ -39,7 +39,7 @@ class _RsDesc(C.Structure):
 
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
-           "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
+           "qrm_detect_host", "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
 
 
 def lib_path() -> str:
@@ -76,6 +76,8 @@ def load_library():
     lib.qrm_rs_decode.restype = C.c_int
     lib.qrm_detect.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.qrm_detect.restype = C.c_int
+    lib.qrm_detect_host.argtypes = [vp, C.POINTER(vp), i32, i32, i32, i32, C.POINTER(vp), i32, i32, vp, vp, vp]
+    lib.qrm_detect_host.restype = C.c_int
     lib.qrm_profile_enable.argtypes = [vp, i32]
     lib.qrm_profile_enable.restype = C.c_int
     lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
@@ -101,6 +103,17 @@ def _dptr(t) -> Optional[int]:
     if t is None:
         return None
     assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous and on the GPU"
+    return t.data_ptr()
+
+
+def _hptr(t) -> Optional[int]:
+    """Host pointer of a CPU torch tensor or a numpy array (or None)."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"], "host arrays must be contiguous"
+        return t.ctypes.data
+    assert not t.is_cuda and t.is_contiguous(), "host tensors must be contiguous and on the CPU"
     return t.data_ptr()
 
 
@@ -209,3 +222,14 @@ class Context:
         self._check(self._lib.qrm_detect(self._h, _dptr(d_images), int(N), int(H), int(W), _dptr(d_off_yx),
                                          int(tile), _dptr(d_logits), _dptr(d_bits), _dptr(d_msg), _dptr(d_codeword),
                                          _dptr(d_nerr), _stream_handle(stream)))
+
+    def qrm_detect_host(self, h_chunks, chunk_images, H, W, h_off_chunks, tile, depth, h_msg, h_codeword, h_nerr):
+        """h_chunks / h_off_chunks: sequences of host buffers (pinned CPU tensors or numpy arrays), one per chunk."""
+        n = len(h_chunks)
+        chunks = (C.c_void_p * max(1, n))(*[_hptr(t) for t in h_chunks])
+        offs = None
+        if h_off_chunks is not None:
+            assert len(h_off_chunks) == n
+            offs = (C.c_void_p * max(1, n))(*[_hptr(t) for t in h_off_chunks])
+        self._check(self._lib.qrm_detect_host(self._h, chunks, int(n), int(chunk_images), int(H), int(W), offs, int(tile),
+                                              int(depth), _hptr(h_msg), _hptr(h_codeword), _hptr(h_nerr)))

@@ -67,12 +67,23 @@ struct qrm_ctx {
     void *d_tables = nullptr;
     // workspace
     int micro_batch = 0; // 0 = default
-    Slot slots[QRM_MAX_STREAMS];
+    Slot slots[QRM_MAX_STREAMS + 1]; // the caller's streams plus the kernel stream of qrm_detect_host
     // optional per-launch timing of the C -> C convolution kernel (hipEvents on the launch stream)
     bool profile = false;
     std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
     size_t ev_used = 0;
     double prof_flops = 0.0;          // algorithmic FLOPs of the timed launches
+    // chunked host -> device pipeline of qrm_detect_host, created on first use: one stream per role
+    // (upload, kernels, download) and a ring of staging buffers with the events that hand them on
+    struct Stage {
+        uint8_t *d_img = nullptr;  // [chunk,3,H,W]
+        int32_t *d_off = nullptr;  // [chunk,2]
+        uint8_t *d_out = nullptr;  // msg [chunk,k] | codeword [chunk,n] | nerr [chunk]
+        size_t img_bytes = 0, out_bytes = 0, off_bytes = 0;
+        hipEvent_t uploaded = nullptr, computed = nullptr, downloaded = nullptr;
+    };
+    Stage stages[QRM_MAX_STREAMS];
+    hipStream_t s_up = nullptr, s_run = nullptr, s_down = nullptr;
     std::string err;
 };
 
@@ -215,7 +226,7 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
     if (!slot)
         for (auto &sl : c->slots)
             if (!sl.used) { slot = &sl; slot->used = true; slot->stream = s; break; }
-    if (!slot) return fail(c, QRM_E_UNSUPPORTED, "more than QRM_MAX_STREAMS streams used with one context");
+    if (!slot) return fail(c, QRM_E_UNSUPPORTED, "more than QRM_MAX_STREAMS caller streams used with one context");
     if (slot->bytes < bytes) {
         if (slot->ws) {
             hipError_t e = hipStreamSynchronize(s);
@@ -491,6 +502,17 @@ void qrm_destroy(qrm_ctx *c)
             if (sl.ws) (void)hipFree(sl.ws);
         }
     for (auto ev : c->ev_pool) (void)hipEventDestroy(ev);
+    for (hipStream_t s : {c->s_up, c->s_run, c->s_down})
+        if (s) (void)hipStreamSynchronize(s);
+    for (auto &sg : c->stages) {
+        if (sg.d_img) (void)hipFree(sg.d_img);
+        if (sg.d_off) (void)hipFree(sg.d_off);
+        if (sg.d_out) (void)hipFree(sg.d_out);
+        for (hipEvent_t ev : {sg.uploaded, sg.computed, sg.downloaded})
+            if (ev) (void)hipEventDestroy(ev);
+    }
+    for (hipStream_t s : {c->s_up, c->s_run, c->s_down})
+        if (s) (void)hipStreamDestroy(s);
     if (c->d_weights) (void)hipFree(c->d_weights);
     if (c->d_tables) (void)hipFree(c->d_tables);
     delete c;
@@ -631,6 +653,124 @@ qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H,
     e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, s);
     if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
     return QRM_OK;
+}
+
+// Grows *p to at least `need` bytes (contents are not kept).
+static qrm_status grow(qrm_ctx *c, void **p, size_t *have, size_t need, hipStream_t s)
+{
+    if (*have >= need) return QRM_OK;
+    if (*p) {
+        hipError_t e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
+        (void)hipFree(*p);
+        *p = nullptr;
+        *have = 0;
+    }
+    hipError_t e = hipMalloc(p, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(c, QRM_E_NOMEM, "staging buffer allocation failed");
+    }
+    *have = need;
+    return QRM_OK;
+}
+
+qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n_chunks, int32_t chunk_images, int32_t H,
+                           int32_t W, const int32_t *const *h_off_chunks, int32_t tile, int32_t depth, uint8_t *h_msg,
+                           uint8_t *h_codeword, int8_t *h_nerr)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_ext || !c->has_rs) return fail(c, QRM_E_INVALID, "context needs both an extractor and a code");
+    if (n_chunks < 0 || chunk_images <= 0) return fail(c, QRM_E_INVALID, "need n_chunks >= 0 and chunk_images > 0");
+    if (depth < 1 || depth > QRM_MAX_STREAMS) return fail(c, QRM_E_INVALID, "depth out of range");
+    if (tile <= 0 || H <= 0 || W <= 0 || tile > H || tile > W || H > 16384 || W > 16384)
+        return fail(c, QRM_E_INVALID, "need 0 < tile <= H, W <= 16384");
+    if (c->n_bits != c->rs.n * c->rs.m) return fail(c, QRM_E_INVALID, "n_bits != n * m");
+    if (n_chunks == 0) return QRM_OK;
+    if (!h_chunks || !h_msg || !h_nerr) return fail(c, QRM_E_INVALID, "h_chunks / h_msg / h_nerr is NULL");
+    for (int i = 0; i < n_chunks; ++i)
+        if (!h_chunks[i] || (h_off_chunks && !h_off_chunks[i])) return fail(c, QRM_E_INVALID, "NULL chunk pointer");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+
+    const size_t img_bytes = (size_t)chunk_images * 3 * H * W, off_bytes = (size_t)chunk_images * 2 * sizeof(int32_t);
+    const int k = c->rs.k, n = c->rs.n;
+    const size_t msg_bytes = (size_t)chunk_images * k, cw_bytes = (size_t)chunk_images * n;
+    const size_t out_bytes = msg_bytes + cw_bytes + (size_t)chunk_images;
+    const int used = depth < n_chunks ? depth : n_chunks;
+    for (hipStream_t *s : {&c->s_up, &c->s_run, &c->s_down})
+        if (!*s) {
+            e = hipStreamCreateWithFlags(s, hipStreamNonBlocking); // default priority
+            if (e != hipSuccess) return hip_fail(c, e, "hipStreamCreateWithFlags");
+        }
+    for (int j = 0; j < used; ++j) {
+        qrm_ctx::Stage &sg = c->stages[j];
+        for (hipEvent_t *ev : {&sg.uploaded, &sg.computed, &sg.downloaded})
+            if (!*ev) {
+                e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+                if (e != hipSuccess) return hip_fail(c, e, "hipEventCreateWithFlags");
+            }
+        qrm_status st = grow(c, (void **)&sg.d_img, &sg.img_bytes, img_bytes, c->s_run);
+        if (st == QRM_OK) st = grow(c, (void **)&sg.d_off, &sg.off_bytes, off_bytes, c->s_run);
+        if (st == QRM_OK) st = grow(c, (void **)&sg.d_out, &sg.out_bytes, out_bytes, c->s_run);
+        if (st != QRM_OK) return st;
+    }
+    // Three streams, one per role.  Uploads follow each other back to back on s_up (the link is the
+    // scarce resource: it should never idle and never be shared by two copies); the kernels of chunk i
+    // run on s_run once its upload is done; its results go home on s_down.  Chunk i uses staging buffer
+    // i mod depth, which is free again when the kernels (input) and the download (output) of chunk
+    // i - depth are done.  Copies of all streams pass through the copy engines in the order they were
+    // submitted and a download waits for its kernels: the download of chunk i-1 is submitted after the
+    // upload of chunk i, so that it never holds up an upload that could already run.
+    qrm_status st = QRM_OK;
+    auto download = [&](int i) -> hipError_t {
+        qrm_ctx::Stage &sg = c->stages[i % used];
+        const uint8_t *d_msg = sg.d_out, *d_cw = sg.d_out + msg_bytes, *d_ne = sg.d_out + msg_bytes + cw_bytes;
+        hipError_t err = hipStreamWaitEvent(c->s_down, sg.computed, 0);
+        if (err == hipSuccess)
+            err = hipMemcpyAsync(h_msg + (size_t)i * msg_bytes, d_msg, msg_bytes, hipMemcpyDeviceToHost, c->s_down);
+        if (err == hipSuccess && h_codeword)
+            err = hipMemcpyAsync(h_codeword + (size_t)i * cw_bytes, d_cw, cw_bytes, hipMemcpyDeviceToHost, c->s_down);
+        if (err == hipSuccess)
+            err = hipMemcpyAsync(h_nerr + (size_t)i * chunk_images, d_ne, chunk_images, hipMemcpyDeviceToHost, c->s_down);
+        if (err == hipSuccess) err = hipEventRecord(sg.downloaded, c->s_down);
+        return err;
+    };
+    int submitted = 0; // chunks whose kernels are enqueued
+    for (int i = 0; i < n_chunks && st == QRM_OK; ++i) {
+        qrm_ctx::Stage &sg = c->stages[i % used];
+        uint8_t *d_msg = sg.d_out, *d_cw = sg.d_out + msg_bytes;
+        int8_t *d_ne = (int8_t *)(sg.d_out + msg_bytes + cw_bytes);
+        e = hipSuccess;
+        if (i >= used) e = hipStreamWaitEvent(c->s_up, sg.computed, 0); // the kernels of chunk i - depth have read d_img
+        if (e == hipSuccess) e = hipMemcpyAsync(sg.d_img, h_chunks[i], img_bytes, hipMemcpyHostToDevice, c->s_up);
+        if (e == hipSuccess && h_off_chunks)
+            e = hipMemcpyAsync(sg.d_off, h_off_chunks[i], off_bytes, hipMemcpyHostToDevice, c->s_up);
+        if (e == hipSuccess) e = hipEventRecord(sg.uploaded, c->s_up);
+        if (e == hipSuccess) e = hipStreamWaitEvent(c->s_run, sg.uploaded, 0);
+        if (e == hipSuccess && i >= used) e = hipStreamWaitEvent(c->s_run, sg.downloaded, 0); // d_out is free again
+        if (e != hipSuccess) { st = hip_fail(c, e, "upload of a chunk"); break; }
+        st = qrm_detect(c, sg.d_img, chunk_images, H, W, h_off_chunks ? sg.d_off : nullptr, tile, nullptr, nullptr, d_msg,
+                        h_codeword ? d_cw : nullptr, d_ne, c->s_run);
+        if (st != QRM_OK) break;
+        e = hipEventRecord(sg.computed, c->s_run);
+        if (e != hipSuccess) { st = hip_fail(c, e, "hipEventRecord"); break; }
+        submitted = i + 1;
+        if (i >= 1) {
+            e = download(i - 1);
+            if (e != hipSuccess) st = hip_fail(c, e, "download of a chunk");
+        }
+    }
+    if (st == QRM_OK && submitted >= 1) {
+        e = download(submitted - 1);
+        if (e != hipSuccess) st = hip_fail(c, e, "download of a chunk");
+    }
+    // the call returns when every chunk is done (also after an error: nothing of ours stays in flight)
+    for (hipStream_t s : {c->s_up, c->s_run, c->s_down}) {
+        e = hipStreamSynchronize(s);
+        if (e != hipSuccess && st == QRM_OK) st = hip_fail(c, e, "hipStreamSynchronize");
+    }
+    return st;
 }
 
 } // extern "C"

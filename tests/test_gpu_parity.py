@@ -329,6 +329,51 @@ def test_detect_on_two_streams(qrm):
     ctx.close()
 
 
+def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
+    """Images in pinned host chunks, streamed through 3 lanes with two of the buffers reused, give exactly
+    what qrm_detect gives on the same images resident in device memory (which the tests above check
+    against the oracle); spot check of the first chunk against the oracle itself."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    chunk, order = 40, [0, 1, 2, 0, 1]               # chunk pointers: buffers 0 and 1 appear twice
+    imgs = synth.images(cfg, 500, 3 * chunk)
+    off = synth.offsets(cfg, 500, 3 * chunk)
+    bufs = [torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, pin_memory=True) for _ in range(3)]
+    obufs = [torch.empty((chunk, 2), dtype=torch.int32, pin_memory=True) for _ in range(3)]
+    for b in range(3):
+        bufs[b].copy_(torch.from_numpy(imgs[b * chunk:(b + 1) * chunk]))
+        obufs[b].copy_(torch.from_numpy(off[b * chunk:(b + 1) * chunk]))
+    n_total = len(order) * chunk
+    h_msg = torch.empty((n_total, cfg.k), dtype=torch.uint8, pin_memory=True)
+    h_cw = torch.empty((n_total, cfg.n), dtype=torch.uint8, pin_memory=True)
+    h_ne = torch.empty((n_total,), dtype=torch.int8, pin_memory=True)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    ctx.qrm_detect_host([bufs[b] for b in order], chunk, cfg.H, cfg.W, [obufs[b] for b in order], cfg.tile, 3,
+                        h_msg, h_cw, h_ne)
+    base = run_detect(ctx, cfg, imgs, off)
+    for i, b in enumerate(order):
+        sl, bl = slice(i * chunk, (i + 1) * chunk), slice(b * chunk, (b + 1) * chunk)
+        assert np.array_equal(h_msg[sl].numpy(), base["msg"][bl])
+        assert np.array_equal(h_cw[sl].numpy(), base["codeword"][bl])
+        assert np.array_equal(h_ne[sl].numpy(), base["nerr"][bl])
+    # a second call on the same context (lanes and staging reused), one stream, no origins, no code words
+    h_msg2 = torch.empty((2 * chunk, cfg.k), dtype=torch.uint8, pin_memory=True)
+    h_ne2 = torch.empty((2 * chunk,), dtype=torch.int8, pin_memory=True)
+    ctx.qrm_detect_host([bufs[2], bufs[0]], chunk, cfg.H, cfg.W, None, cfg.tile, 1, h_msg2, None, h_ne2)
+    base0 = run_detect(ctx, cfg, np.concatenate([imgs[2 * chunk:], imgs[:chunk]]), None)
+    assert np.array_equal(h_msg2.numpy(), base0["msg"]) and np.array_equal(h_ne2.numpy(), base0["nerr"])
+    # oracle on a few images of the first chunk: RS outputs follow from the GPU's own hard bits
+    ns = 4
+    ref = oracle.detect(wts, imgs[:ns], off[:ns], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    if np.array_equal(base["bits"][:ns], ref["bits"]):
+        assert np.array_equal(h_msg[:ns].numpy(), ref["msg"]) and np.array_equal(h_ne[:ns].numpy(), ref["nerr"])
+    with pytest.raises(qrm.QrmError) as e:
+        ctx.qrm_detect_host([bufs[0]], chunk, cfg.H, cfg.W, None, cfg.tile, 0, h_msg, None, h_ne)
+    assert e.value.status == qrm.QRM_E_INVALID
+    ctx.qrm_detect_host([], chunk, cfg.H, cfg.W, None, cfg.tile, 2, h_msg, None, h_ne)   # zero chunks: no-op
+    ctx.close()
+
+
 # ---------------------------------------------------------------- error paths (host side only)
 
 def test_error_statuses(qrm):
