@@ -611,6 +611,265 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Two consecutive C -> C blocks in one kernel (tiles of at most one column block, C = 64).
+//
+// conv_mid is bound by activation traffic as much as by the matrix cores (288 FLOP per byte against a
+// machine balance of ~310).  Here the activations between the two blocks never leave the CU: a
+// workgroup walks down one image, group A (wavefronts 0-3, weights of the first block) turns input rows
+// into rows of the intermediate activation map, which it writes as bf16 into a second LDS ring, and
+// group B (wavefronts 4-7, weights of the second block) turns those into output rows.  Global traffic
+// per FLOP halves; both wavefronts of a SIMD carry matrix work, so each fills the other's gaps.
+//
+// Rows are processed two at a time (the two rings of 8 rows of 66 pixels x 144 bytes fill the LDS).  Step s
+// of an image of h rows, S = ceil(h/2):
+//   all : issue the direct-to-LDS loads of input rows 2s+5, 2s+6 (needed in step s+2)
+//   A   : s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
+//         bf16 -> intermediate ring (zeros outside the tile);  s == S: rows 2S, 2S+1 = zero padding
+//   B   : first the epilogue of the rows it accumulated in step s-1 (stores behind which its matrix
+//         instructions then run), then output rows 2j, 2j+1, j = s-2, from intermediate rows 2j-1 .. 2j+2
+//   end : s_waitcnt vmcnt(0) (everything issued at the start of the step has had the step to finish),
+//         one workgroup barrier
+// Row y of either map lives in ring slot (y + 2) mod 8.
+// The second block's weights are rounded so that the rounding residuals of the nine taps of every
+// (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
+// image, so there are no channel means to correct its bias with.
+// ------------------------------------------------------------------------------------------------
+constexpr int kPairRing = 8;
+
+struct PairArgs {
+    const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
+    int in_slots;
+    const float *rsum;  // [c_in][c_out] residual-weight sums of the first block (fp32), or nullptr
+    float *tout;        // records of the output's sampled channel sums [n_img][kPairSub][stat_rec(C,1)], or nullptr
+    int ipw;            // images per workgroup
+};
+constexpr int kPairSub = 2; // statistics records per image: one per pixel-block pair of wavefronts of group B
+
+template <int C>
+__global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__restrict__ ws, uint32_t in_off, ConvGeom g,
+                                                           const bf16_t *__restrict__ wfragA,
+                                                           const bf16_t *__restrict__ wfragB,
+                                                           const float *__restrict__ biasA,
+                                                           const float *__restrict__ biasB, PairArgs st,
+                                                           bf16_t *__restrict__ out)
+{
+    typedef MidCfg<C> K;
+    static_assert(K::NCB == 2, "the pair kernel is written for 64 channels");
+    constexpr int RW = 2;
+    constexpr int ROWB = kHaloW * K::PS;          // staged rows are packed: 66 pixels x 144 bytes
+    constexpr int SLOTS = ROWB / 16;              // 16-byte slots per row
+    constexpr int PIECES = (SLOTS + 63) / 64;     // wavefront-wide loads per row, the last one partial
+    __shared__ __attribute__((aligned(1024))) uint8_t ring_in[kPairRing * ROWB];
+    __shared__ __attribute__((aligned(16))) uint8_t ring_mid[kPairRing * ROWB];
+    __shared__ __attribute__((aligned(16))) float s_initA[C]; // first block: bias + rounding-residual correction of the image
+    __shared__ __attribute__((aligned(16))) float s_biasB[C];
+    __shared__ __attribute__((aligned(16))) float s_stat[4][32];
+    __shared__ __attribute__((aligned(16))) float s_mean[4][C];
+    __shared__ float s_cnt[4];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, w4 = wave & 3;
+    const int px = lane & 31, half = lane >> 5;
+    const int cb = w4 & 1, xb = w4 >> 1;
+
+    bf16x8 Wr[9][K::KC];
+    load_weight_frags<C>(Wr, grp == 0 ? wfragA : wfragB, cb, lane);
+
+    const int vb = xcd_virtual_block(blockIdx.x, gridDim.x);
+    const int n_begin = vb * st.ipw, n_end = min(g.n_img, n_begin + st.ipw);
+    if (n_begin >= n_end) return;
+    const int S = (g.h + 1) / 2;
+    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
+    const lrow_t in_base = lds_address(ring_in) + (xb * 32 + px) * K::PS + half * 16;
+    const lrow_t mid_base = lds_address(ring_mid) + (xb * 32 + px) * K::PS + half * 16;
+    const int sample_phase = min(3, g.strips - 1);
+    auto slot_of = [](int y) { return (y + 2) & (kPairRing - 1); };
+
+    // loads of input row y of image n into its ring slot: piece q of the row by wavefront q mod 8
+    auto issue_row = [&](int n, int y) {
+        const int ln = pin_in_loop(tid & 63);
+        const bool rowok = y >= 0 && y < g.h;
+        const uint32_t rowoff = in_off + (uint32_t)n * img_bytes + (uint32_t)(y * g.w * C * 2);
+        uint8_t *dst = ring_in + slot_of(y) * ROWB;
+#pragma unroll
+        for (int q0 = 0; q0 < PIECES; q0 += 8) {
+            const int q = q0 + wave;
+            if (q < PIECES) {
+                const int sl = q * 64 + ln;
+                const int col = sl / K::SPP, cpos = sl - col * K::SPP;
+                const int gx = col - 1;
+                const bool ok = rowok && cpos < C / 8 && gx >= 0 && gx < g.w;
+                const uint32_t off = ok ? rowoff + (uint32_t)((gx * C + cpos * 8) * 2) : 0u;
+                if (sl < SLOTS) // (the last piece of a row is partial: the next row starts right behind it)
+                    __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(dst + q * 1024), 16, 0, 0);
+            }
+        }
+    };
+    // s_initA[o] = biasA[o] + sum_c rsum[c][o] * mean_n[c], by the four wavefronts of group A
+    auto prepare_init = [&](int n) {
+        constexpr int OPW = C / 4, PARTS = 64 / OPW, CP = C / PARTS;
+        const int ln = pin_in_loop(tid & 63);
+        const int o = w4 * OPW + ln % OPW, part = ln / OPW;
+        float d = 0.f;
+        if (st.tin && st.rsum) {
+            if (ln < C) {
+                float sum = 0.f, cnt = 0.f;
+                for (int s2 = 0; s2 < st.in_slots; ++s2) {
+                    const float *rec = st.tin + ((int64_t)n * st.in_slots + s2) * stat_rec(C, 1);
+                    sum += rec[ln];
+                    cnt += rec[C];
+                }
+                s_mean[w4][ln] = cnt > 0.f ? sum / cnt : 0.f;
+            }
+#pragma unroll 4
+            for (int k = 0; k < CP; ++k) {
+                const int c = part * CP + k;
+                d = fmaf(st.rsum[c * C + o], s_mean[w4][c], d);
+            }
+#pragma unroll
+            for (int sh = OPW; sh < 64; sh <<= 1) d += __shfl_xor(d, sh);
+        }
+        if (part == 0) s_initA[o] = biasA[o] + d;
+    };
+
+    // ---- once per workgroup: second block's bias, the halo columns of the intermediate ring, statistics
+    if (grp == 1) {
+        if (tid - 256 < C) s_biasB[tid - 256] = biasB[tid - 256];
+        if (lane < 32) s_stat[w4][lane] = 0.f;
+        if (lane == 0) s_cnt[w4] = 0.f;
+    }
+    for (int i = tid; i < kPairRing * 2 * (K::PS / 16); i += 512) { // columns -1 and w.. stay zero for good
+        const int row = i / (2 * (K::PS / 16)), rem = i - row * 2 * (K::PS / 16);
+        const int side = rem / (K::PS / 16), sl = rem - side * (K::PS / 16);
+        *(u32x4 *)(ring_mid + row * ROWB + (side ? (kHaloW - 1) : 0) * K::PS + sl * 16) = (u32x4){0u, 0u, 0u, 0u};
+    }
+
+    f32x16 acc[RW];
+    for (int n = n_begin; n < n_end; ++n) {
+        // ---- image prologue: correction of this image, input rows -1 .. 4, intermediate row -1 = zero
+        if (grp == 0) prepare_init(n);
+#pragma unroll 1
+        for (int y = -1; y <= 4; ++y) issue_row(n, y);
+        if (grp == 1)
+            for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        lds_barrier();
+
+#pragma unroll 1
+        for (int s = 0; s <= S + 2; ++s) {
+            if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
+            if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
+            if (grp == 0) {
+                const int ln = pin_in_loop(tid & 63);
+                const int pxl = ln & 31, hf = ln >> 5;
+                const int x = xb * 32 + pxl;
+                if (s < S) {
+                    lrow_t rowp[RW + 2];
+#pragma unroll
+                    for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * s - 1 + r) * ROWB;
+                    strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                    // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
+                    const float *si = &s_initA[cb * 32 + hf * 16];
+#pragma unroll
+                    for (int hq = 0; hq < 2; ++hq) {
+                        const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                        for (int r = 0; r < RW; ++r) {
+                            const int y = 2 * s + r;
+                            u32x4 pk;
+                            pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
+                            pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
+                            pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
+                            pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                            if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
+                            *(u32x4 *)(ring_mid + slot_of(y) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
+                        }
+                    }
+                } else if (s == S) { // the rows below the tile: zero padding of the second block
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+#pragma unroll
+                        for (int hq = 0; hq < 2; ++hq)
+                            *(u32x4 *)(ring_mid + slot_of(2 * s + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
+                                (u32x4){0u, 0u, 0u, 0u};
+                }
+            } else {
+                const int ln = pin_in_loop(tid & 63);
+                const int pxl = ln & 31, hf = ln >> 5;
+                const int x = xb * 32 + pxl;
+                if (s >= 3 && s - 3 < S) { // epilogue of the rows accumulated in the previous step
+                    const int j = s - 3;
+                    const float *si = &s_biasB[cb * 32 + hf * 16];
+                    const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+#pragma unroll
+                    for (int hq = 0; hq < 2; ++hq) {
+                        const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                        for (int r = 0; r < RW; ++r) {
+                            u32x4 pk;
+                            pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
+                            pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
+                            pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
+                            pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                            if (2 * j + r < g.h && x < g.w) *(u32x4 *)(out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq)) = pk;
+                        }
+                    }
+                    if (st.tout && ((j >> 1) & 7) == sample_phase) { // the rows conv_mid would sample
+                        float *my_stat = &s_stat[w4][hf * 16];
+                        const bool colok = x < g.w;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 bq = *(const f32x4 *)(si + 4 * q);
+                            float tv[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int r = 0; r < RW; ++r)
+                                if (2 * j + r < g.h) {
+#pragma unroll
+                                    for (int e = 0; e < 4; ++e) tv[e] += fmaxf(acc[r][4 * q + e] + bq[e], 0.f);
+                                }
+                            if (!colok) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) tv[e] = 0.f;
+                            }
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) tv[e] = half_sum(tv[e]);
+                            lds_accumulate4(my_stat + 4 * q, tv, pxl == kSumLane);
+                        }
+                        if (cb == 0 && ln == 0) {
+                            const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
+                            s_cnt[w4] += (float)(rows * cols);
+                        }
+                    }
+                }
+                if (s >= 2 && s - 2 < S) {
+                    const int j = s - 2;
+                    lrow_t rowp[RW + 2];
+#pragma unroll
+                    for (int r = 0; r < RW + 2; ++r) rowp[r] = mid_base + (uint32_t)slot_of(2 * j - 1 + r) * ROWB;
+                    strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                }
+            }
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            lds_barrier();
+        }
+        // ---- this image's sampled channel sums -> its records; accumulators cleared
+        if (grp == 1 && st.tout) {
+            const int ln = pin_in_loop(tid & 63);
+            float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, 1);
+            if (ln < 32) {
+                rec[cb * 32 + ln] = s_stat[w4][ln];
+                s_stat[w4][ln] = 0.f;
+            }
+            if (cb == 0 && ln == 0) {
+                rec[C] = s_cnt[w4];
+                s_cnt[w4] = 0.f;
+            }
+        }
+    }
+}
+
 // Final conv C -> 64 output channels per grid.y slice, summed over the pixels of one (image, column
 // block).  partial[n][colblk*2 + xb][slice*64 + cb*32 + half*16 + v]
 template <int C, bool RELU>
@@ -1053,6 +1312,23 @@ hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g
         if (last) hipLaunchKernelGGL((conv_mid_kernel<32, MODE_LAST>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
         else hipLaunchKernelGGL((conv_mid_kernel<32, MODE_MID>), grid, block, 0, s, ws, in_off, g, wfrag, bias, st, out);
     }
+    return hipGetLastError();
+}
+
+bool conv_pair_supported(int C, const ConvGeom &g) { return C == 64 && g.colblks == 1; }
+
+int conv_pair_records_per_image() { return kPairSub; }
+
+hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag_a,
+                            const bf16_t *wfrag_b, const float *bias_a, const float *bias_b, const float *tin,
+                            int in_slots, const float *rsum_a, float *tout, int num_cu, bf16_t *out, hipStream_t s)
+{
+    if (!conv_pair_supported(C, g)) return hipErrorInvalidValue;
+    const int ipw = (g.n_img + num_cu - 1) / num_cu;
+    const int blocks = (g.n_img + ipw - 1) / ipw;
+    PairArgs st{tin, in_slots, rsum_a, tout, ipw};
+    hipLaunchKernelGGL((conv_pair_kernel<64>), dim3(blocks), dim3(512), 0, s, ws, in_off, g, wfrag_a, wfrag_b, bias_a, bias_b,
+                       st, out);
     return hipGetLastError();
 }
 

@@ -62,6 +62,7 @@ struct qrm_ctx {
     const float *d_rsum = nullptr;        // [(n_blocks-1)][C][C] weight-rounding residual sums of the C -> C layers
     const float *d_wft = nullptr;         // final conv, fp32, [C*9][nbp]
     bool collapse = false;                // final conv + pool evaluated in closed form from channel sums
+    int pairable = 0;                     // the first `pairable` C -> C layers may run as fused pairs (even number)
     // code
     RsParams rs{};
     void *d_tables = nullptr;
@@ -103,7 +104,38 @@ qrm_status hip_fail(qrm_ctx *c, hipError_t e, const char *what)
 // ---- weights -> MFMA A-fragment order ------------------------------------------------------------
 // fragment element (blk, tap, kc, lane, e): output channel blk*32 + perm32(lane%32),
 // input channel kc*16 + (lane/32)*8 + e.  w is OIHW [cout][cin][3][3]; rows >= cout are zero.
-void pack_mid(const float *w, const float *scale, int cout, int cout_pad, int cin, std::vector<uint16_t> &dst)
+float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+// bf16 values of one layer's (scaled) weights, [o][ci][tap].  diffuse = false: each weight rounded to
+// nearest even.  diffuse = true: error feedback over the nine taps of every (o, ci) pair - each tap is
+// rounded after the residual of the taps before it has been added - so that the residuals of the nine
+// taps sum to (almost) nothing: the part of the rounding error that acts on the mean activation, the
+// only part that global average pooling does not wash out, is gone without any correction term.
+std::vector<uint16_t> round_layer(const float *w, const float *scale, int cout, int cin, bool diffuse)
+{
+    std::vector<uint16_t> r((size_t)cout * cin * 9);
+    for (int o = 0; o < cout; ++o)
+        for (int ci = 0; ci < cin; ++ci) {
+            double carry = 0.0;
+            for (int tap = 0; tap < 9; ++tap) {
+                const size_t i = ((size_t)o * cin + ci) * 9 + tap;
+                const float v = w[i] * (scale ? scale[o] : 1.f);
+                const float target = diffuse ? (float)((double)v + carry) : v;
+                r[i] = f32_to_bf16_rne(target);
+                carry = (double)v + carry - (double)bf16_to_f32(r[i]);
+                if (!diffuse) carry = 0.0;
+            }
+        }
+    return r;
+}
+
+void pack_mid(const std::vector<uint16_t> &r, int cout, int cout_pad, int cin, std::vector<uint16_t> &dst)
 {
     const int KC = cin / 16;
     for (int blk = 0; blk < cout_pad / 32; ++blk)
@@ -113,22 +145,12 @@ void pack_mid(const float *w, const float *scale, int cout, int cout_pad, int ci
                     for (int e = 0; e < 8; ++e) {
                         const int o = blk * 32 + perm32(lane & 31);
                         const int ci = kc * 16 + (lane >> 5) * 8 + e;
-                        float v = 0.f;
-                        if (o < cout) v = w[((size_t)o * cin + ci) * 9 + tap] * (scale ? scale[o] : 1.f);
-                        dst.push_back(f32_to_bf16_rne(v));
+                        dst.push_back(o < cout ? r[((size_t)o * cin + ci) * 9 + tap] : (uint16_t)0);
                     }
 }
 
 // first layer: k = q*16 + (lane/32)*8 + e  ->  tap = k/4 (0..8, beyond: zero), channel = k%4 (3: zero).
 // Per output block two fragment sets: bf16(w) and bf16(w - bf16(w)).
-float bf16_to_f32(uint16_t h)
-{
-    uint32_t u = (uint32_t)h << 16;
-    float f;
-    memcpy(&f, &u, 4);
-    return f;
-}
-
 void pack_first(const float *w, const float *scale, int cout, std::vector<uint16_t> &dst)
 {
     for (int blk = 0; blk < cout / 32; ++blk)
@@ -149,16 +171,16 @@ void pack_first(const float *w, const float *scale, int cout, std::vector<uint16
 // rsum[o][c] = sum over the 9 taps of (w*scale - bf16(w*scale)): what the bf16 weights leave out, as it
 // acts on a spatially constant input
 // appended as [c_in][c_out]: the lanes of the kernel that applies it run over c_out
-void residual_sums(const float *w, const float *scale, int C, std::vector<float> &dst)
+void residual_sums(const float *w, const float *scale, const std::vector<uint16_t> &r, int C, std::vector<float> &dst)
 {
     for (int ci = 0; ci < C; ++ci)
         for (int o = 0; o < C; ++o) {
-            double r = 0.0;
+            double s = 0.0;
             for (int tap = 0; tap < 9; ++tap) {
-                const float v = w[((size_t)o * C + ci) * 9 + tap] * (scale ? scale[o] : 1.f);
-                r += (double)v - (double)bf16_to_f32(f32_to_bf16_rne(v));
+                const size_t i = ((size_t)o * C + ci) * 9 + tap;
+                s += (double)(w[i] * (scale ? scale[o] : 1.f)) - (double)bf16_to_f32(r[i]);
             }
-            dst.push_back((float)r);
+            dst.push_back((float)s);
         }
 }
 
@@ -287,9 +309,17 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
         if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
         const int blocks = n_run > 0 ? n_run : c->n_blocks;
-        for (int b = 1; b < blocks; ++b) {
-            hipEvent_t ev0 = nullptr, ev1 = nullptr;
-            if (c->profile) {
+        // C -> C layers m = b - 1: layers (m, m + 1), m even, below c->pairable run as one fused launch when
+        // the tile is a single column block; the others one launch each.  While timing is on, the launches of
+        // the dominant kind (pairs if any run, else single layers) are bracketed by events.
+        static const bool no_pairs = getenv("QRM_DISABLE_PAIRS") != nullptr; // A/B switch for measurements
+        const bool pairs_here = !no_pairs && c->pairable >= 2 && conv_pair_supported(c->C, g) && blocks >= 3;
+        for (int b = 1; b < blocks;) {
+            const int m = b - 1;
+            const bool pair = pairs_here && (m & 1) == 0 && m + 1 < c->pairable && b + 1 < blocks;
+            const bool timed = c->profile && pair == pairs_here;
+            hipEvent_t ev1 = nullptr;
+            if (timed) {
                 if (c->ev_used + 2 > c->ev_pool.size()) {
                     for (int i = 0; i < 2; ++i) {
                         hipEvent_t ev;
@@ -298,23 +328,32 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
                         c->ev_pool.push_back(ev);
                     }
                 }
-                ev0 = c->ev_pool[c->ev_used];
+                hipEvent_t ev0 = c->ev_pool[c->ev_used];
                 ev1 = c->ev_pool[c->ev_used + 1];
                 c->ev_used += 2;
                 (void)hipEventRecord(ev0, s);
             }
-            const bool last = n_run < 0 && c->collapse && b == c->n_blocks - 1;
-            e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[b - 1], c->d_bias + (size_t)b * c->C, tb[tcur],
-                                in_slots, c->d_rsum + (size_t)(b - 1) * c->C * c->C, tb[tcur ^ 1], pm, last,
-                                buf[cur ^ 1], s);
-            if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
-            if (c->profile) {
+            const float *rsum = c->d_rsum + (size_t)m * c->C * c->C;
+            if (pair) {
+                e = launch_conv_pair(base, buf_off[cur], g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1], c->d_bias + (size_t)b * c->C,
+                                     c->d_bias + (size_t)(b + 1) * c->C, tb[tcur], in_slots, rsum, tb[tcur ^ 1], c->num_cu,
+                                     buf[cur ^ 1], s);
+                if (e != hipSuccess) return hip_fail(c, e, "conv_pair launch");
+                in_slots = conv_pair_records_per_image();
+            } else {
+                const bool last = n_run < 0 && c->collapse && b == c->n_blocks - 1;
+                e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[m], c->d_bias + (size_t)b * c->C, tb[tcur], in_slots,
+                                    rsum, tb[tcur ^ 1], pm, last, buf[cur ^ 1], s);
+                if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
+                in_slots = pm.slots * pm.sub;
+            }
+            if (timed) {
                 (void)hipEventRecord(ev1, s);
-                c->prof_flops += 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
+                c->prof_flops += (pair ? 2.0 : 1.0) * 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
             }
             cur ^= 1;
             tcur ^= 1;
-            in_slots = pm.slots * pm.sub;
+            b += pair ? 2 : 1;
         }
         if (n_run > 0) {
             e = launch_nhwc_to_nchw(buf[cur], cnt, h, w, c->C, d_act + n0 * (int64_t)c->C * h * w, s);
@@ -417,15 +456,21 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         frag_off.push_back(frag.size());
         pack_first(w, ext->scale, C, frag);
         w += (size_t)C * 3 * 9;
+        c->collapse = nb >= 2 && !c->final_relu;
+        // C -> C layers that can run as the second block of a fused pair (see launch_conv_pair) get
+        // residual-cancelling rounding: layers 2, 4, .. of the C -> C layers before the last block
+        c->pairable = C == 64 ? ((nb - 1) - (c->collapse ? 1 : 0)) / 2 * 2 : 0;
+        std::vector<std::vector<uint16_t>> rounded; // per C -> C layer
         for (int b = 1; b < nb; ++b) {
+            const int m = b - 1;
+            rounded.push_back(round_layer(w, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, C, (m & 1) && m < c->pairable));
             frag_off.push_back(frag.size());
-            pack_mid(w, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, C, C, frag);
+            pack_mid(rounded.back(), C, C, C, frag);
             w += (size_t)C * C * 9;
         }
         frag_off.push_back(frag.size());
-        pack_mid(w, c->final_affine ? ext->scale + (size_t)nb * C : nullptr, nbits, nbp, C, frag);
+        pack_mid(round_layer(w, c->final_affine ? ext->scale + (size_t)nb * C : nullptr, nbits, C, false), nbits, nbp, C, frag);
 
-        c->collapse = nb >= 2 && !c->final_relu;
         std::vector<float> fl; // biases [nb*C], final bias [nbp], lin_w, lin_b, residual sums, final conv (fp32)
         for (int i = 0; i < nb * C; ++i) fl.push_back(ext->bias ? ext->bias[i] : 0.f);
         const size_t off_fb = fl.size();
@@ -439,7 +484,7 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         {
             const float *wm = ext->conv_w + (size_t)C * 3 * 9;
             for (int b = 1; b < nb; ++b) {
-                residual_sums(wm, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, fl);
+                residual_sums(wm, ext->scale ? ext->scale + (size_t)b * C : nullptr, rounded[b - 1], C, fl);
                 wm += (size_t)C * C * 9;
             }
         }
