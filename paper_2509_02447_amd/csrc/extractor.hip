@@ -623,13 +623,12 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 //
 // Rows are processed two at a time (the two rings of 8 rows of 66 pixels x 144 bytes fill the LDS).  Step s
 // of an image of h rows, S = ceil(h/2):
-//   all : issue the direct-to-LDS loads of input rows 2s+5, 2s+6 (needed in step s+2)
-//   A   : s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
+//   A   : issue the direct-to-LDS loads of input rows 2s+5, 2s+6 (needed in step s+2);
+//         s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
 //         bf16 -> intermediate ring (zeros outside the tile);  s == S: rows 2S, 2S+1 = zero padding
 //   B   : first the epilogue of the rows it accumulated in step s-1 (stores behind which its matrix
 //         instructions then run), then output rows 2j, 2j+1, j = s-2, from intermediate rows 2j-1 .. 2j+2
-//   end : s_waitcnt vmcnt(0) (everything issued at the start of the step has had the step to finish),
-//         one workgroup barrier
+//   end : A: s_waitcnt vmcnt(0) (its loads have had the step to land); one workgroup barrier
 // Row y of either map lives in ring slot (y + 2) mod 8.
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
 // (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
@@ -687,22 +686,30 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     const int sample_phase = min(3, g.strips - 1);
     auto slot_of = [](int y) { return (y + 2) & (kPairRing - 1); };
 
-    // loads of input row y of image n into its ring slot: piece q of the row by wavefront q mod 8
+    // Loads of input row y of image n into its ring slot, by group A (which has slack: group B's path
+    // through a step is the longer one): piece q of the row by wavefront q mod 4.  What a lane loads
+    // within a row does not change: byte offset of its slot in an image row (kSlotZero: zeros; kSlotNone:
+    // no slot - the last piece of a row is partial, the next row starts right behind it).
+    constexpr int QPW = (PIECES + 3) / 4;
+    constexpr uint32_t kSlotNone = 0xfffffffeu;
+    uint32_t lane_off[QPW];
+#pragma unroll
+    for (int k = 0; k < QPW; ++k) {
+        const int sl = (w4 + 4 * k) * 64 + lane;
+        const int col = sl / K::SPP, cpos = sl - col * K::SPP;
+        const int gx = col - 1;
+        lane_off[k] = sl >= SLOTS ? kSlotNone : (cpos < C / 8 && gx >= 0 && gx < g.w) ? (uint32_t)((gx * C + cpos * 8) * 2) : kSlotZero;
+    }
     auto issue_row = [&](int n, int y) {
-        const int ln = pin_in_loop(tid & 63);
         const bool rowok = y >= 0 && y < g.h;
         const uint32_t rowoff = in_off + (uint32_t)n * img_bytes + (uint32_t)(y * g.w * C * 2);
         uint8_t *dst = ring_in + slot_of(y) * ROWB;
 #pragma unroll
-        for (int q0 = 0; q0 < PIECES; q0 += 8) {
-            const int q = q0 + wave;
+        for (int k = 0; k < QPW; ++k) {
+            const int q = w4 + 4 * k;
             if (q < PIECES) {
-                const int sl = q * 64 + ln;
-                const int col = sl / K::SPP, cpos = sl - col * K::SPP;
-                const int gx = col - 1;
-                const bool ok = rowok && cpos < C / 8 && gx >= 0 && gx < g.w;
-                const uint32_t off = ok ? rowoff + (uint32_t)((gx * C + cpos * 8) * 2) : 0u;
-                if (sl < SLOTS) // (the last piece of a row is partial: the next row starts right behind it)
+                const uint32_t off = (rowok && lane_off[k] < kSlotNone) ? rowoff + lane_off[k] : 0u;
+                if (lane_off[k] != kSlotNone)
                     __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(dst + q * 1024), 16, 0, 0);
             }
         }
@@ -750,8 +757,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     for (int n = n_begin; n < n_end; ++n) {
         // ---- image prologue: correction of this image, input rows -1 .. 4, intermediate row -1 = zero
         if (grp == 0) prepare_init(n);
+        if (grp == 0) {
 #pragma unroll 1
-        for (int y = -1; y <= 4; ++y) issue_row(n, y);
+            for (int y = -1; y <= 4; ++y) issue_row(n, y);
+        }
         if (grp == 1)
             for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
@@ -759,9 +768,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 
 #pragma unroll 1
         for (int s = 0; s <= S + 2; ++s) {
-            if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
-            if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
             if (grp == 0) {
+                if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
+                if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
                 const int ln = pin_in_loop(tid & 63);
                 const int pxl = ln & 31, hf = ln >> 5;
                 const int x = xb * 32 + pxl;
@@ -803,6 +812,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     const int j = s - 3;
                     const float *si = &s_biasB[cb * 32 + hf * 16];
                     const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+                    const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
 #pragma unroll
                     for (int hq = 0; hq < 2; ++hq) {
                         const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
@@ -813,7 +823,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                             pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
                             pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
                             pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
-                            if (2 * j + r < g.h && x < g.w) *(u32x4 *)(out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq)) = pk;
+                            bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                            if (full) *(u32x4 *)dst = pk;
+                            else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
                         }
                     }
                     if (st.tout && ((j >> 1) & 7) == sample_phase) { // the rows conv_mid would sample
@@ -851,7 +863,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
                 }
             }
-            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            // group A: the loads issued at the start of the step have had the step to land.  Group B only
+            // stores, and nothing ever waits for those.
+            if (grp == 0) __builtin_amdgcn_s_waitcnt(kWaitVm0);
             lds_barrier();
         }
         // ---- this image's sampled channel sums -> its records; accumulators cleared
