@@ -623,12 +623,12 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 //
 // Rows are processed two at a time (the two rings of 8 rows of 66 pixels x 144 bytes fill the LDS).  Step s
 // of an image of h rows, S = ceil(h/2):
-//   A   : issue the direct-to-LDS loads of input rows 2s+5, 2s+6 (needed in step s+2);
-//         s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
+//   A   : s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
 //         bf16 -> intermediate ring (zeros outside the tile);  s == S: rows 2S, 2S+1 = zero padding
 //   B   : first the epilogue of the rows it accumulated in step s-1 (stores behind which its matrix
 //         instructions then run), then output rows 2j, 2j+1, j = s-2, from intermediate rows 2j-1 .. 2j+2
-//   end : A: s_waitcnt vmcnt(0) (its loads have had the step to land); one workgroup barrier
+//   end : A: s_waitcnt vmcnt(0) (the loads it issued a step ago), then the direct-to-LDS loads of input
+//         rows 2s+5, 2s+6 (needed in step s+2); one workgroup barrier
 // Row y of either map lives in ring slot (y + 2) mod 8.
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
 // (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
@@ -769,8 +769,6 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll 1
         for (int s = 0; s <= S + 2; ++s) {
             if (grp == 0) {
-                if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
-                if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
                 const int ln = pin_in_loop(tid & 63);
                 const int pxl = ln & 31, hf = ln >> 5;
                 const int x = xb * 32 + pxl;
@@ -863,9 +861,14 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
                 }
             }
-            // group A: the loads issued at the start of the step have had the step to land.  Group B only
-            // stores, and nothing ever waits for those.
-            if (grp == 0) __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            // Group A, at the end of its step (it has slack, group B's path is the longer one): the loads it
+            // issued a step ago have landed, then the rows needed two steps from now are put on their way.
+            // Group B only stores, and nothing ever waits for those.
+            if (grp == 0) {
+                __builtin_amdgcn_s_waitcnt(kWaitVm0);
+                if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
+                if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
+            }
             lds_barrier();
         }
         // ---- this image's sampled channel sums -> its records; accumulators cleared
