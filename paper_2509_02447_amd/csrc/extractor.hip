@@ -627,8 +627,8 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 //         bf16 -> intermediate ring (zeros outside the tile);  s == S: rows 2S, 2S+1 = zero padding
 //   B   : first the epilogue of the rows it accumulated in step s-1 (stores behind which its matrix
 //         instructions then run), then output rows 2j, 2j+1, j = s-2, from intermediate rows 2j-1 .. 2j+2
-//   end : A: s_waitcnt vmcnt(0) (the loads it issued a step ago), then the direct-to-LDS loads of input
-//         rows 2s+5, 2s+6 (needed in step s+2); one workgroup barrier
+//   end : s_waitcnt vmcnt(0) (the loads issued a step ago), then the direct-to-LDS loads of input rows
+//         2s+5 (group A) and 2s+6 (group B), needed in step s+2; one workgroup barrier
 // Row y of either map lives in ring slot (y + 2) mod 8.
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
 // (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
@@ -686,8 +686,8 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     const int sample_phase = min(3, g.strips - 1);
     auto slot_of = [](int y) { return (y + 2) & (kPairRing - 1); };
 
-    // Loads of input row y of image n into its ring slot, by group A (which has slack: group B's path
-    // through a step is the longer one): piece q of the row by wavefront q mod 4.  What a lane loads
+    // Loads of input row y of image n into its ring slot by the four wavefronts of one group: piece q of
+    // the row by wavefront q mod 4.  What a lane loads
     // within a row does not change: byte offset of its slot in an image row (kSlotZero: zeros; kSlotNone:
     // no slot - the last piece of a row is partial, the next row starts right behind it).
     constexpr int QPW = (PIECES + 3) / 4;
@@ -757,10 +757,8 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     for (int n = n_begin; n < n_end; ++n) {
         // ---- image prologue: correction of this image, input rows -1 .. 4, intermediate row -1 = zero
         if (grp == 0) prepare_init(n);
-        if (grp == 0) {
 #pragma unroll 1
-            for (int y = -1; y <= 4; ++y) issue_row(n, y);
-        }
+        for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y);
         if (grp == 1)
             for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
@@ -861,14 +859,11 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
                 }
             }
-            // Group A, at the end of its step (it has slack, group B's path is the longer one): the loads it
-            // issued a step ago have landed, then the rows needed two steps from now are put on their way.
-            // Group B only stores, and nothing ever waits for those.
-            if (grp == 0) {
-                __builtin_amdgcn_s_waitcnt(kWaitVm0);
-                if (2 * s + 5 <= 2 * S) issue_row(n, 2 * s + 5);
-                if (2 * s + 6 <= 2 * S) issue_row(n, 2 * s + 6);
-            }
+            // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
+            // date from the start of this step) is done, then the rows needed two steps from now are put on
+            // their way, one row per group.
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            if (2 * s + 5 + grp <= 2 * S) issue_row(n, 2 * s + 5 + grp);
             lds_barrier();
         }
         // ---- this image's sampled channel sums -> its records; accumulators cleared
