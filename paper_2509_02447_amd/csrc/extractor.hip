@@ -299,6 +299,70 @@ __device__ __forceinline__ void lds_accumulate4(float *slot4, const float (&tv)[
     }
 }
 
+// Channel sums of the RW output rows (first row yw, column x) held in `acc`, after bias `si` (this lane's
+// 16 channels) and ReLU, added to this wavefront's accumulators `my_stat` ([sum index][32 channels] floats,
+// already offset to the lane's 16 channels).  LAST = false: sum index 0 only (the whole strip).  LAST = true:
+// the nine border-aware sums of the last block: 0 all, 1 / 2 first / last row, 3 / 4 first / last column,
+// 5 .. 8 the corners (top-left, top-right, bottom-left, bottom-right).  Four channels at a time: registers
+// are scarce next to weights and accumulators.
+template <int RW, bool LAST>
+__device__ __forceinline__ void strip_statistics(const f32x16 (&acc)[RW], const float *si, float *my_stat, int x, int yw,
+                                                 int h, int w, int px)
+{
+    const bool colok = x < w;
+    const int rl = h - 1 - yw; // image row h-1 relative to this wavefront's rows
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f32x4 bq = *(const f32x4 *)(si + 4 * q);
+        float tv[4] = {0.f, 0.f, 0.f, 0.f}; // sum over this wavefront's valid rows of relu(output)
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+            if (yw + r < h) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) tv[e] += fmaxf(acc[r][4 * q + e] + bq[e], 0.f);
+            }
+        if (!colok) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tv[e] = 0.f;
+        }
+        if (LAST) {
+            lds_accumulate4(my_stat + 3 * 32 + 4 * q, tv, x == 0);       // first column
+            lds_accumulate4(my_stat + 4 * 32 + 4 * q, tv, x == w - 1);   // last column
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) tv[e] = half_sum(tv[e]);
+        lds_accumulate4(my_stat + 4 * q, tv, px == kSumLane);            // whole tile (or its sampled strips)
+        if (LAST) {
+            if (yw == 0) { // image row 0 is this wavefront's first row
+                float rv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rv[e] = colok ? fmaxf(acc[0][4 * q + e] + bq[e], 0.f) : 0.f;
+                lds_accumulate4(my_stat + 5 * 32 + 4 * q, rv, x == 0);
+                lds_accumulate4(my_stat + 6 * 32 + 4 * q, rv, x == w - 1);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
+                lds_accumulate4(my_stat + 1 * 32 + 4 * q, rv, px == kSumLane);
+            }
+            if (rl >= 0 && rl < RW) {
+                float rv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float a = acc[0][4 * q + e];
+#pragma unroll
+                    for (int r = 1; r < RW; ++r) a = rl == r ? acc[r][4 * q + e] : a;
+                    rv[e] = colok ? fmaxf(a + bq[e], 0.f) : 0.f;
+                }
+                lds_accumulate4(my_stat + 7 * 32 + 4 * q, rv, x == 0);
+                lds_accumulate4(my_stat + 8 * 32 + 4 * q, rv, x == w - 1);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
+                lds_accumulate4(my_stat + 2 * 32 + 4 * q, rv, px == kSumLane);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 struct StatArgs {
     const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
     int in_slots;
@@ -493,59 +557,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
             }
         }
         if (st.tout && (MODE == MODE_LAST || (strip & 7) == sample_phase)) {
-            // four channels at a time (registers are scarce next to weights and accumulators)
-            const bool colok = x < g.w;
-            const int rl = g.h - 1 - yw; // image row h-1 relative to this wavefront's rows
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 bq = *(const f32x4 *)(si + 4 * q);
-                float tv[4] = {0.f, 0.f, 0.f, 0.f}; // sum over this wavefront's valid rows of relu(output)
-#pragma unroll
-                for (int r = 0; r < RW; ++r)
-                    if (yw + r < g.h) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) tv[e] += fmaxf(acc[r][4 * q + e] + bq[e], 0.f);
-                    }
-                if (!colok) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) tv[e] = 0.f;
-                }
-                if (MODE == MODE_LAST) {
-                    lds_accumulate4(my_stat + 3 * 32 + 4 * q, tv, x == 0);         // first column
-                    lds_accumulate4(my_stat + 4 * 32 + 4 * q, tv, x == g.w - 1);   // last column
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) tv[e] = half_sum(tv[e]);
-                lds_accumulate4(my_stat + 4 * q, tv, px == kSumLane);              // whole tile (or its sampled strips)
-                if (MODE == MODE_LAST) {
-                    if (yw == 0) { // image row 0 is this wavefront's first row
-                        float rv[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) rv[e] = colok ? fmaxf(acc[0][4 * q + e] + bq[e], 0.f) : 0.f;
-                        lds_accumulate4(my_stat + 5 * 32 + 4 * q, rv, x == 0);
-                        lds_accumulate4(my_stat + 6 * 32 + 4 * q, rv, x == g.w - 1);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
-                        lds_accumulate4(my_stat + 1 * 32 + 4 * q, rv, px == kSumLane);
-                    }
-                    if (rl >= 0 && rl < RW) {
-                        float rv[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            float a = acc[0][4 * q + e];
-#pragma unroll
-                            for (int r = 1; r < RW; ++r) a = rl == r ? acc[r][4 * q + e] : a;
-                            rv[e] = colok ? fmaxf(a + bq[e], 0.f) : 0.f;
-                        }
-                        lds_accumulate4(my_stat + 7 * 32 + 4 * q, rv, x == 0);
-                        lds_accumulate4(my_stat + 8 * 32 + 4 * q, rv, x == g.w - 1);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) rv[e] = half_sum(rv[e]);
-                        lds_accumulate4(my_stat + 2 * 32 + 4 * q, rv, px == kSumLane);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            strip_statistics<RW, MODE == MODE_LAST>(acc, si, my_stat, x, yw, g.h, g.w, px);
             if (cb == 0 && lane == 0) {
                 const int rows = max(0, min(RW, g.h - yw)), cols = max(0, min(32, g.w - (x0 + xb * 32)));
                 s_cnt[wave] += (float)(rows * cols);
@@ -640,14 +652,19 @@ struct PairArgs {
     const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
     int in_slots;
     const float *rsum;  // [c_in][c_out] residual-weight sums of the first block (fp32), or nullptr
-    float *tout;        // records of the output's sampled channel sums [n_img][kPairSub][stat_rec(C,1)], or nullptr
+    float *tout;        // records of the output's channel sums [n_img][kPairSub][stat_rec(C, 1 or 9)], or nullptr
     int ipw;            // images per workgroup
 };
 constexpr int kPairSub = 2; // statistics records per image: one per pixel-block pair of wavefronts of group B
 
-template <int C>
-__global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__restrict__ ws, uint32_t in_off, ConvGeom g,
-                                                           const bf16_t *__restrict__ wfragA,
+// FIRST: the first of the two blocks is the network's first block (3 -> C on the raw u8 tile: crop and
+//        normalisation fused, weights as bf16 high part + residual, see conv_first_kernel) instead of a
+//        C -> C block; `src` replaces ws / in_off, wfragA holds that block's fragments.
+// LASTB: the second block is the network's last block: no activations are written, its records carry the
+//        nine border-aware channel sums (see strip_statistics).
+template <int C, bool FIRST, bool LASTB>
+__global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__restrict__ ws, uint32_t in_off, TileSrc src,
+                                                           ConvGeom g, const bf16_t *__restrict__ wfragA,
                                                            const bf16_t *__restrict__ wfragB,
                                                            const float *__restrict__ biasA,
                                                            const float *__restrict__ biasB, PairArgs st,
@@ -656,14 +673,16 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     typedef MidCfg<C> K;
     static_assert(K::NCB == 2, "the pair kernel is written for 64 channels");
     constexpr int RW = 2;
+    constexpr int NQ = LASTB ? 9 : 1;
     constexpr int ROWB = kHaloW * K::PS;          // staged rows are packed: 66 pixels x 144 bytes
     constexpr int SLOTS = ROWB / 16;              // 16-byte slots per row
     constexpr int PIECES = (SLOTS + 63) / 64;     // wavefront-wide loads per row, the last one partial
-    __shared__ __attribute__((aligned(1024))) uint8_t ring_in[kPairRing * ROWB];
+    __shared__ __attribute__((aligned(1024))) uint8_t ring_in[FIRST ? 1024 : kPairRing * ROWB];
     __shared__ __attribute__((aligned(16))) uint8_t ring_mid[kPairRing * ROWB];
-    __shared__ __attribute__((aligned(16))) float s_initA[C]; // first block: bias + rounding-residual correction of the image
+    __shared__ __attribute__((aligned(16))) uint16_t s_pix[FIRST ? kPairRing : 1][kHaloW][4]; // normalised bf16 pixels, channel 3 = 0
+    __shared__ __attribute__((aligned(16))) float s_initA[C]; // first block: bias (+ rounding-residual correction of the image)
     __shared__ __attribute__((aligned(16))) float s_biasB[C];
-    __shared__ __attribute__((aligned(16))) float s_stat[4][32];
+    __shared__ __attribute__((aligned(16))) float s_stat[4][NQ][32];
     __shared__ __attribute__((aligned(16))) float s_mean[4][C];
     __shared__ float s_cnt[4];
 
@@ -673,8 +692,17 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     const int px = lane & 31, half = lane >> 5;
     const int cb = w4 & 1, xb = w4 >> 1;
 
+    // C -> C weights (group B; group A unless FIRST).  Group A with FIRST keeps the first block's weights in
+    // the same registers: Wr[p][k] = high part (p = 0) / residual (p = 1) of 16-wide k chunk k = 0..2.
     bf16x8 Wr[9][K::KC];
-    load_weight_frags<C>(Wr, grp == 0 ? wfragA : wfragB, cb, lane);
+    if (FIRST && grp == 0) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int k = 0; k < 3; ++k) Wr[p][k] = ((const bf16x8 *)wfragA)[((cb * 2 + p) * 3 + k) * 64 + lane];
+    } else {
+        load_weight_frags<C>(Wr, grp == 0 ? wfragA : wfragB, cb, lane);
+    }
 
     const int vb = xcd_virtual_block(blockIdx.x, gridDim.x);
     const int n_begin = vb * st.ipw, n_end = min(g.n_img, n_begin + st.ipw);
@@ -687,9 +715,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     auto slot_of = [](int y) { return (y + 2) & (kPairRing - 1); };
 
     // Loads of input row y of image n into its ring slot by the four wavefronts of one group: piece q of
-    // the row by wavefront q mod 4.  What a lane loads
-    // within a row does not change: byte offset of its slot in an image row (kSlotZero: zeros; kSlotNone:
-    // no slot - the last piece of a row is partial, the next row starts right behind it).
+    // the row by wavefront q mod 4.  What a lane loads within a row does not change: byte offset of its
+    // slot in an image row (kSlotZero: zeros; kSlotNone: no slot - the last piece of a row is partial, the
+    // next row starts right behind it).
     constexpr int QPW = (PIECES + 3) / 4;
     constexpr uint32_t kSlotNone = 0xfffffffeu;
     uint32_t lane_off[QPW];
@@ -740,12 +768,41 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         }
         if (part == 0) s_initA[o] = biasA[o] + d;
     };
+    // FIRST: rows of the raw tile -> normalised bf16 pixels in s_pix, by the 256 threads of group A.
+    // Element e of a row pair: row e / 198, channel (e % 198) / 66, staged column (e % 198) % 66.
+    constexpr int kRowElems = 3 * kHaloW;
+    const float ka[3] = {src.inv_std[0] * (1.0f / 255.0f), src.inv_std[1] * (1.0f / 255.0f), src.inv_std[2] * (1.0f / 255.0f)};
+    const float kb[3] = {-src.mean[0] * src.inv_std[0], -src.mean[1] * src.inv_std[1], -src.mean[2] * src.inv_std[2]};
+    const int plane = src.H * src.W;
+    auto pixel_fetch = [&](const uint8_t *tile0, int y0, int e, bool &inside) -> uint8_t {
+        const int row = e / kRowElems, rem = e - row * kRowElems;
+        const int c = rem / kHaloW, col = rem - c * kHaloW;
+        const int ty = y0 + row, tx = col - 1;
+        inside = e < 2 * kRowElems && ty >= 0 && ty < g.h && tx >= 0 && tx < g.w;
+        return inside ? tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx] : (uint8_t)0;
+    };
+    auto pixel_store = [&](int y0, int e, uint8_t v, bool inside) {
+        if (e < 2 * kRowElems) {
+            const int row = e / kRowElems, rem = e - row * kRowElems;
+            const int c = rem / kHaloW, col = rem - c * kHaloW;
+            const float a = c == 0 ? ka[0] : (c == 1 ? ka[1] : ka[2]);
+            const float b = c == 0 ? kb[0] : (c == 1 ? kb[1] : kb[2]);
+            const float f = inside ? fmaf((float)v, a, b) : 0.f;
+            s_pix[slot_of(y0 + row)][col][c] = __builtin_bit_cast(uint16_t, (bf16_t)f);
+        }
+    };
 
-    // ---- once per workgroup: second block's bias, the halo columns of the intermediate ring, statistics
+    // ---- once per workgroup: biases, the halo columns of the intermediate ring, statistics
     if (grp == 1) {
         if (tid - 256 < C) s_biasB[tid - 256] = biasB[tid - 256];
-        if (lane < 32) s_stat[w4][lane] = 0.f;
+        if (lane < 32) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) s_stat[w4][q][lane] = 0.f;
+        }
         if (lane == 0) s_cnt[w4] = 0.f;
+    } else if (FIRST) {
+        if (tid < C) s_initA[tid] = biasA[tid];
+        for (int i = tid; i < kPairRing * kHaloW; i += 256) s_pix[i / kHaloW][i % kHaloW][3] = 0; // the padding channel
     }
     for (int i = tid; i < kPairRing * 2 * (K::PS / 16); i += 512) { // columns -1 and w.. stay zero for good
         const int row = i / (2 * (K::PS / 16)), rem = i - row * 2 * (K::PS / 16);
@@ -755,14 +812,34 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 
     f32x16 acc[RW];
     for (int n = n_begin; n < n_end; ++n) {
-        // ---- image prologue: correction of this image, input rows -1 .. 4, intermediate row -1 = zero
-        if (grp == 0) prepare_init(n);
+        // ---- image prologue: correction of this image, input rows -1 .. 4 (FIRST: -1 .. 2), intermediate row -1 = zero
+        const uint8_t *tile0 = nullptr;
+        if (FIRST) {
+            int oy = 0, ox = 0;
+            if (src.off) {
+                oy = clampi(src.off[2 * n], 0, src.H - g.h);
+                ox = clampi(src.off[2 * n + 1], 0, src.W - g.w);
+            }
+            tile0 = src.img + (int64_t)n * 3 * plane + (int64_t)oy * src.W + ox;
+            if (grp == 0) {
 #pragma unroll 1
-        for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y);
+                for (int y0 = -1; y0 <= 1; y0 += 2)
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        bool inside;
+                        const uint8_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside);
+                        pixel_store(y0, tid + 256 * k, v, inside);
+                    }
+            }
+        } else {
+            if (grp == 0) prepare_init(n);
+#pragma unroll 1
+            for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y);
+        }
         if (grp == 1)
             for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        lds_barrier();
+        __syncthreads();
 
 #pragma unroll 1
         for (int s = 0; s <= S + 2; ++s) {
@@ -770,11 +847,50 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 const int ln = pin_in_loop(tid & 63);
                 const int pxl = ln & 31, hf = ln >> 5;
                 const int x = xb * 32 + pxl;
-                if (s < S) {
-                    lrow_t rowp[RW + 2];
+                // FIRST: the raw pixels of rows 2s+3, 2s+4 (window of step s+1) start their way into registers
+                uint8_t pv[2] = {0, 0};
+                bool pin[2] = {false, false};
+                if (FIRST && 2 * s + 3 <= 2 * S) {
 #pragma unroll
-                    for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * s - 1 + r) * ROWB;
-                    strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, 2 * s + 3, tid + 256 * k, pin[k]);
+                }
+                if (s < S) {
+                    if (FIRST) {
+                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int r = 0; r < RW; ++r) {
+                            const int y = 2 * s + r;
+                            const uint8_t *lp[3];
+#pragma unroll
+                            for (int dy = 0; dy < 3; ++dy) lp[dy] = (const uint8_t *)&s_pix[slot_of(y - 1 + dy)][xb * 32 + pxl][0];
+                            bf16x8 bfrag[3];
+#pragma unroll
+                            for (int k = 0; k < 3; ++k) { // k chunk: taps 4k + 2 hf and 4k + 2 hf + 1 (beyond 8: zero weights, tap 8 re-read)
+                                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                                u32x2 two[2];
+#pragma unroll
+                                for (int j2 = 0; j2 < 2; ++j2) {
+                                    int tap = 4 * k + 2 * hf + j2;
+                                    tap = tap > 8 ? 8 : tap;
+                                    const int dy = tap / 3, dx = tap - dy * 3;
+                                    const uint8_t *p0 = dy == 0 ? lp[0] : (dy == 1 ? lp[1] : lp[2]);
+                                    two[j2] = *(const u32x2 *)(p0 + dx * 8);
+                                }
+                                const u32x4 both = {two[0][0], two[0][1], two[1][0], two[1][1]};
+                                bfrag[k] = __builtin_bit_cast(bf16x8, both);
+                            }
+                            acc[r] = mfma32(Wr[0][0], bfrag[0], zero);
+                            acc[r] = mfma32(Wr[0][1], bfrag[1], acc[r]);
+                            acc[r] = mfma32(Wr[0][2], bfrag[2], acc[r]);
+#pragma unroll
+                            for (int k = 0; k < 3; ++k) acc[r] = mfma32(Wr[1][k], bfrag[k], acc[r]);
+                        }
+                    } else {
+                        lrow_t rowp[RW + 2];
+#pragma unroll
+                        for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * s - 1 + r) * ROWB;
+                        strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                    }
                     // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
                     const float *si = &s_initA[cb * 32 + hf * 16];
 #pragma unroll
@@ -800,6 +916,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                             *(u32x4 *)(ring_mid + slot_of(2 * s + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
                                 (u32x4){0u, 0u, 0u, 0u};
                 }
+                if (FIRST && 2 * s + 3 <= 2 * S) { // their slots were last read two steps ago
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) pixel_store(2 * s + 3, tid + 256 * k, pv[k], pin[k]);
+                }
             } else {
                 const int ln = pin_in_loop(tid & 63);
                 const int pxl = ln & 31, hf = ln >> 5;
@@ -807,44 +927,27 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 if (s >= 3 && s - 3 < S) { // epilogue of the rows accumulated in the previous step
                     const int j = s - 3;
                     const float *si = &s_biasB[cb * 32 + hf * 16];
-                    const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
-                    const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
+                    if (!LASTB) {
+                        const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+                        const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
 #pragma unroll
-                    for (int hq = 0; hq < 2; ++hq) {
-                        const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+                        for (int hq = 0; hq < 2; ++hq) {
+                            const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
-                        for (int r = 0; r < RW; ++r) {
-                            u32x4 pk;
-                            pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
-                            pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
-                            pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
-                            pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
-                            bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
-                            if (full) *(u32x4 *)dst = pk;
-                            else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                            for (int r = 0; r < RW; ++r) {
+                                u32x4 pk;
+                                pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
+                                pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
+                                pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
+                                pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                                bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                                if (full) *(u32x4 *)dst = pk;
+                                else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                            }
                         }
                     }
-                    if (st.tout && ((j >> 1) & 7) == sample_phase) { // the rows conv_mid would sample
-                        float *my_stat = &s_stat[w4][hf * 16];
-                        const bool colok = x < g.w;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const f32x4 bq = *(const f32x4 *)(si + 4 * q);
-                            float tv[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                            for (int r = 0; r < RW; ++r)
-                                if (2 * j + r < g.h) {
-#pragma unroll
-                                    for (int e = 0; e < 4; ++e) tv[e] += fmaxf(acc[r][4 * q + e] + bq[e], 0.f);
-                                }
-                            if (!colok) {
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) tv[e] = 0.f;
-                            }
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) tv[e] = half_sum(tv[e]);
-                            lds_accumulate4(my_stat + 4 * q, tv, pxl == kSumLane);
-                        }
+                    if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
+                        strip_statistics<RW, LASTB>(acc, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
                         if (cb == 0 && ln == 0) {
                             const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
                             s_cnt[w4] += (float)(rows * cols);
@@ -862,20 +965,25 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
             // date from the start of this step) is done, then the rows needed two steps from now are put on
             // their way, one row per group.
-            __builtin_amdgcn_s_waitcnt(kWaitVm0);
-            if (2 * s + 5 + grp <= 2 * S) issue_row(n, 2 * s + 5 + grp);
+            if (!FIRST) {
+                __builtin_amdgcn_s_waitcnt(kWaitVm0);
+                if (2 * s + 5 + grp <= 2 * S) issue_row(n, 2 * s + 5 + grp);
+            }
             lds_barrier();
         }
-        // ---- this image's sampled channel sums -> its records; accumulators cleared
+        // ---- this image's channel sums -> its records; accumulators cleared
         if (grp == 1 && st.tout) {
             const int ln = pin_in_loop(tid & 63);
-            float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, 1);
+            float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, NQ);
             if (ln < 32) {
-                rec[cb * 32 + ln] = s_stat[w4][ln];
-                s_stat[w4][ln] = 0.f;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    rec[q * C + cb * 32 + ln] = s_stat[w4][q][ln];
+                    s_stat[w4][q][ln] = 0.f;
+                }
             }
             if (cb == 0 && ln == 0) {
-                rec[C] = s_cnt[w4];
+                rec[NQ * C] = s_cnt[w4];
                 s_cnt[w4] = 0.f;
             }
         }
@@ -1331,16 +1439,23 @@ bool conv_pair_supported(int C, const ConvGeom &g) { return C == 64 && g.colblks
 
 int conv_pair_records_per_image() { return kPairSub; }
 
-hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag_a,
-                            const bf16_t *wfrag_b, const float *bias_a, const float *bias_b, const float *tin,
-                            int in_slots, const float *rsum_a, float *tout, int num_cu, bf16_t *out, hipStream_t s)
+hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const TileSrc *first, const ConvGeom &g, int C,
+                            const bf16_t *wfrag_a, const bf16_t *wfrag_b, const float *bias_a, const float *bias_b,
+                            const float *tin, int in_slots, const float *rsum_a, float *tout, bool last, int num_cu,
+                            bf16_t *out, hipStream_t s)
 {
     if (!conv_pair_supported(C, g)) return hipErrorInvalidValue;
     const int ipw = (g.n_img + num_cu - 1) / num_cu;
-    const int blocks = (g.n_img + ipw - 1) / ipw;
+    const dim3 grid((g.n_img + ipw - 1) / ipw), block(512);
     PairArgs st{tin, in_slots, rsum_a, tout, ipw};
-    hipLaunchKernelGGL((conv_pair_kernel<64>), dim3(blocks), dim3(512), 0, s, ws, in_off, g, wfrag_a, wfrag_b, bias_a, bias_b,
-                       st, out);
+    const TileSrc src = first ? *first : TileSrc{};
+    if (first) {
+        if (last) hipLaunchKernelGGL((conv_pair_kernel<64, true, true>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        else hipLaunchKernelGGL((conv_pair_kernel<64, true, false>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+    } else {
+        if (last) hipLaunchKernelGGL((conv_pair_kernel<64, false, true>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        else hipLaunchKernelGGL((conv_pair_kernel<64, false, false>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+    }
     return hipGetLastError();
 }
 

@@ -62,7 +62,7 @@ struct qrm_ctx {
     const float *d_rsum = nullptr;        // [(n_blocks-1)][C][C] weight-rounding residual sums of the C -> C layers
     const float *d_wft = nullptr;         // final conv, fp32, [C*9][nbp]
     bool collapse = false;                // final conv + pool evaluated in closed form from channel sums
-    int pairable = 0;                     // the first `pairable` C -> C layers may run as fused pairs (even number)
+    bool pairable = false;                // weights are prepared for the fused schedule (see qrm_create)
     // code
     RsParams rs{};
     void *d_tables = nullptr;
@@ -306,18 +306,29 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         src.img = img0 + n0 * 3 * (int64_t)src.H * src.W;
         src.off = off0 ? off0 + 2 * n0 : nullptr;
         int cur = 0, tcur = 0, in_slots = pf.slots * pf.sub;
-        e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
-        if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
-        const int blocks = n_run > 0 ? n_run : c->n_blocks;
-        // C -> C layers m = b - 1: layers (m, m + 1), m even, below c->pairable run as one fused launch when
-        // the tile is a single column block; the others one launch each.  While timing is on, the launches of
-        // the dominant kind (pairs if any run, else single layers) are bracketed by events.
+        const int blocks = n_run > 0 ? n_run : c->n_blocks; // blocks to run: the first one and C -> C layers m = b - 1
+        // Fused schedule when the tile is a single column block: [first + layer 0], (1,2), (3,4), ..; what is
+        // left over runs alone.  While timing is on, the launches of the dominant kind (fused C -> C pairs if
+        // any run, else single C -> C layers) are bracketed by events.
         static const bool no_pairs = getenv("QRM_DISABLE_PAIRS") != nullptr; // A/B switch for measurements
-        const bool pairs_here = !no_pairs && c->pairable >= 2 && conv_pair_supported(c->C, g) && blocks >= 3;
-        for (int b = 1; b < blocks;) {
+        const bool fused = !no_pairs && c->pairable && conv_pair_supported(c->C, g) && blocks >= 2;
+        const bool time_pairs = fused && blocks >= 4;
+        auto is_last = [&](int b) { return n_run < 0 && c->collapse && b == c->n_blocks - 1; };
+        int b = 1;
+        if (fused) {
+            e = launch_conv_pair(base, 0, &src, g, c->C, c->d_w_first, c->d_w_mid[0], c->d_bias, c->d_bias + (size_t)c->C, nullptr,
+                                 0, nullptr, tb[tcur], is_last(1), c->num_cu, buf[cur], s);
+            if (e != hipSuccess) return hip_fail(c, e, "conv_pair (first) launch");
+            in_slots = conv_pair_records_per_image();
+            b = 2;
+        } else {
+            e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
+            if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
+        }
+        while (b < blocks) {
             const int m = b - 1;
-            const bool pair = pairs_here && (m & 1) == 0 && m + 1 < c->pairable && b + 1 < blocks;
-            const bool timed = c->profile && pair == pairs_here;
+            const bool pair = fused && (m & 1) == 1 && b + 1 < blocks;
+            const bool timed = c->profile && pair == time_pairs;
             hipEvent_t ev1 = nullptr;
             if (timed) {
                 if (c->ev_used + 2 > c->ev_pool.size()) {
@@ -335,15 +346,14 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
             }
             const float *rsum = c->d_rsum + (size_t)m * c->C * c->C;
             if (pair) {
-                e = launch_conv_pair(base, buf_off[cur], g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1], c->d_bias + (size_t)b * c->C,
-                                     c->d_bias + (size_t)(b + 1) * c->C, tb[tcur], in_slots, rsum, tb[tcur ^ 1], c->num_cu,
-                                     buf[cur ^ 1], s);
+                e = launch_conv_pair(base, buf_off[cur], nullptr, g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1],
+                                     c->d_bias + (size_t)b * c->C, c->d_bias + (size_t)(b + 1) * c->C, tb[tcur], in_slots, rsum,
+                                     tb[tcur ^ 1], is_last(b + 1), c->num_cu, buf[cur ^ 1], s);
                 if (e != hipSuccess) return hip_fail(c, e, "conv_pair launch");
                 in_slots = conv_pair_records_per_image();
             } else {
-                const bool last = n_run < 0 && c->collapse && b == c->n_blocks - 1;
                 e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[m], c->d_bias + (size_t)b * c->C, tb[tcur], in_slots,
-                                    rsum, tb[tcur ^ 1], pm, last, buf[cur ^ 1], s);
+                                    rsum, tb[tcur ^ 1], pm, is_last(b), buf[cur ^ 1], s);
                 if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
                 in_slots = pm.slots * pm.sub;
             }
@@ -457,13 +467,15 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         pack_first(w, ext->scale, C, frag);
         w += (size_t)C * 3 * 9;
         c->collapse = nb >= 2 && !c->final_relu;
-        // C -> C layers that can run as the second block of a fused pair (see launch_conv_pair) get
-        // residual-cancelling rounding: layers 2, 4, .. of the C -> C layers before the last block
-        c->pairable = C == 64 ? ((nb - 1) - (c->collapse ? 1 : 0)) / 2 * 2 : 0;
+        // Fused schedule (launch_conv_pair; C = 64, tiles of one column block): [first block + C -> C layer 0],
+        // then C -> C layers (1,2), (3,4), ..; a layer left over runs alone.  The second block of a fused
+        // launch - the even C -> C layers - cannot have its bias corrected with channel means of its input
+        // (that input never exists as a whole image): those layers get residual-cancelling rounding instead.
+        c->pairable = C == 64;
         std::vector<std::vector<uint16_t>> rounded; // per C -> C layer
         for (int b = 1; b < nb; ++b) {
             const int m = b - 1;
-            rounded.push_back(round_layer(w, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, C, (m & 1) && m < c->pairable));
+            rounded.push_back(round_layer(w, ext->scale ? ext->scale + (size_t)b * C : nullptr, C, C, c->pairable && (m & 1) == 0));
             frag_off.push_back(frag.size());
             pack_mid(rounded.back(), C, C, C, frag);
             w += (size_t)C * C * 9;

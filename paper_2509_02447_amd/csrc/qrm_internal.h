@@ -68,15 +68,19 @@ hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g
                            const float *bias, const float *tin, int in_slots, const float *rsum, float *tout,
                            const Partition &part, bool last, bf16_t *out, hipStream_t s);
 
-// Two consecutive C -> C blocks in one launch, the activations between them staying in LDS (tiles of one
-// column block, C = 64: conv_pair_supported).  Weights / bias of both blocks; tin / in_slots / rsum_a as
-// for launch_conv_mid (first block only: the second block's weights are rounded so that it needs no
-// correction); tout: sampled channel sums of the output, conv_pair_records_per_image() records per image.
+// Two consecutive blocks in one launch, the activations between them staying in LDS (tiles of one column
+// block, C = 64: conv_pair_supported).  first != nullptr: the first of the two is the network's first block
+// (raw u8 tiles, wfrag_a / bias_a of that block; ws / in_off / tin / rsum_a unused); otherwise both are
+// C -> C blocks and tin / in_slots / rsum_a are as for launch_conv_mid (first block only: the second block's
+// weights are rounded so that it needs no correction).  last: the second block is the network's last one
+// (no activations written, nine sums per channel in the records).  tout: channel sums of the output,
+// conv_pair_records_per_image() records per image.
 bool conv_pair_supported(int C, const ConvGeom &g);
 int conv_pair_records_per_image();
-hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag_a,
-                            const bf16_t *wfrag_b, const float *bias_a, const float *bias_b, const float *tin,
-                            int in_slots, const float *rsum_a, float *tout, int num_cu, bf16_t *out, hipStream_t s);
+hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const TileSrc *first, const ConvGeom &g, int C,
+                            const bf16_t *wfrag_a, const bf16_t *wfrag_b, const float *bias_a, const float *bias_b,
+                            const float *tin, int in_slots, const float *rsum_a, float *tout, bool last, int num_cu,
+                            bf16_t *out, hipStream_t s);
 
 // nine channel sums of the last block -> final conv + average pool in closed form -> linear -> logits,
 // bits, symbols.  wft: final conv weights fp32, [C*9][nbp] (k = c*9 + tap major)
