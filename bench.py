@@ -5,9 +5,9 @@ One step = one pass of the whole hot path (tile crop + normalise fused into the 
 the convolutional extractor, thresholding, symbol packing, Reed-Solomon decoding) over the 4096-image
 "tiled detection" configuration, with images, origins and weights already resident in device memory.
 
-Prints ONE JSON line: images/s (whole job), the roofline of the dominant kernel (the C -> C 3x3
-convolution on the bf16 matrix cores; duration per launch measured with HIP events on the launch
-stream), per-stage figures for the tile-crop and Reed-Solomon kernels, and the CPU oracle timed on
+Prints ONE JSON line: images/s (whole job), the roofline of the dominant kernel (the fused pair of
+C -> C 3x3 convolution blocks on the bf16 matrix cores; duration per launch measured with HIP events on
+the launch stream), per-stage figures for the tile-crop and Reed-Solomon kernels, and the CPU oracle timed on
 this machine's host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -26,8 +26,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# copy kernel of known size (profiles/conv_mid_c2_hbm_traffic.txt), for the default micro-batch of 256 images.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 274027688  # 133.13 MiB read + 128.20 MiB written; algorithmic 2 x 128 MiB
+# copy kernel of known size (profiles/conv_pair_c2_hbm_traffic.txt), for the fused pair of C -> C blocks at the
+# default micro-batch of 256 images: 129.57 MiB read + 128.14 MiB written; algorithmic 2 x 128 MiB.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 270228282
 
 
 def main() -> int:
@@ -112,13 +113,16 @@ def main() -> int:
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    k_ms, k_launches, k_flops = ctx.qrm_profile_read()
+    k_ms, k_launches, k_flops, blocks_per_launch = ctx.qrm_profile_read()
     ctx.qrm_profile_enable(False)
     achieved_tflops = k_flops / (k_ms * 1e-3) / 1e12 if k_ms > 0 else 0.0
-    roofline = {"kernel": "conv_mid_kernel (3x3 conv C->C, bf16 MFMA implicit GEMM)", "bound": "mfma",
+    kname = ("conv_pair_kernel<64,false,false> (two fused 3x3 conv blocks C->C, bf16 MFMA implicit GEMM, activations between "
+             "them in LDS)") if blocks_per_launch >= 2 else "conv_mid_kernel (3x3 conv C->C, bf16 MFMA implicit GEMM)"
+    roofline = {"kernel": kname, "bound": "mfma",
                 "achieved": round(achieved_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (blocks_per_launch == 2 and args.config == "C2" and not args.micro_batch
+                                                                 and not args.images) else None,
                 "launches": int(k_launches), "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),
                 "flops_per_launch": k_flops / max(1, k_launches),
                 "timing": "HIP events around every launch, second pass of the same steps"}
@@ -153,7 +157,8 @@ def main() -> int:
         "rs_decode": {"us": round(t_rs * 1e6, 2), "codewords_per_s": round(n_cw / t_rs, 0),
                       "algorithmic_GBs": round(rs_bytes / t_rs / 1e9, 2),
                       "frac_hbm": round(rs_bytes / t_rs / 1e9 / PEAK_HBM_GBS, 5), "codewords": n_cw},
-        # MFMA work actually executed per image: first conv + the C -> C convs.  The final conv + average
+        # MFMA work actually executed per image: first conv + the C -> C convs, over the whole step (all
+        # kernels, launch gaps and the RS decode included in the time).  The final conv + average
         # pool is evaluated in closed form from nine channel sums of the last block (it is linear), so its
         # 2*9*C*n_bits*l^2 FLOPs are NOT credited here.
         "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),

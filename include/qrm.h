@@ -196,14 +196,17 @@ QRM_API qrm_status qrm_detect_host(qrm_ctx *ctx, const uint8_t *const *h_chunks,
                                    uint8_t *h_msg, uint8_t *h_codeword, int8_t *h_nerr);
 
 /*
- * Per-launch timing of the dominant kernel (the C -> C convolution), for benchmarks: while enabled,
- * every launch of that kernel is bracketed by two hipEvents recorded on the stream it is launched on.
- * qrm_profile_read waits for the recorded events, returns the summed duration in milliseconds, the
- * number of launches and their algorithmic FLOPs (2*9*C*C*h*w per image), and clears the record.
+ * Per-launch timing of the dominant kernel, for benchmarks: while enabled, every launch of that kernel is
+ * bracketed by two hipEvents recorded on the stream it is launched on.  The dominant kernel is the fused
+ * pair of C -> C convolution blocks when the configuration runs any (64 channels, tiles up to 64 wide),
+ * otherwise the single C -> C convolution block.  qrm_profile_read waits for the recorded events, returns
+ * the summed duration in milliseconds, the number of launches and their algorithmic FLOPs (2*9*C*C*h*w
+ * per image and block) and the number of blocks one timed launch computes (1 or 2), and clears the record.
  * Any output pointer may be NULL.
  */
 QRM_API qrm_status qrm_profile_enable(qrm_ctx *ctx, int32_t on);
-QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, double *ms_total, int64_t *launches, double *flops);
+QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, double *ms_total, int64_t *launches, double *flops,
+                                    int32_t *blocks_per_launch);
 
 /* Library version string, e.g. "qrm 0.1 gfx950". */
 QRM_API const char *qrm_version(void);

@@ -80,7 +80,8 @@ def load_library():
     lib.qrm_detect_host.restype = C.c_int
     lib.qrm_profile_enable.argtypes = [vp, i32]
     lib.qrm_profile_enable.restype = C.c_int
-    lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
+                                     C.POINTER(C.c_int32)]
     lib.qrm_profile_read.restype = C.c_int
     lib.qrm_version.argtypes = []
     lib.qrm_version.restype = C.c_char_p
@@ -193,10 +194,10 @@ class Context:
         self._check(self._lib.qrm_profile_enable(self._h, int(bool(on))))
 
     def qrm_profile_read(self):
-        """-> (milliseconds, launches, algorithmic FLOPs) of the C -> C convolution launches since enable."""
-        ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
-        self._check(self._lib.qrm_profile_read(self._h, C.byref(ms), C.byref(n), C.byref(fl)))
-        return ms.value, n.value, fl.value
+        """-> (milliseconds, launches, algorithmic FLOPs, blocks per launch) of the timed launches since enable."""
+        ms, n, fl, bp = C.c_double(), C.c_int64(), C.c_double(), C.c_int32()
+        self._check(self._lib.qrm_profile_read(self._h, C.byref(ms), C.byref(n), C.byref(fl), C.byref(bp)))
+        return ms.value, n.value, fl.value, bp.value
 
     def qrm_workspace_bytes(self, N: int, tile_h: int, tile_w: int) -> int:
         return int(self._lib.qrm_workspace_bytes(self._h, int(N), int(tile_h), int(tile_w)))

@@ -74,6 +74,7 @@ struct qrm_ctx {
     std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
     size_t ev_used = 0;
     double prof_flops = 0.0;          // algorithmic FLOPs of the timed launches
+    int prof_blocks = 1;              // convolution blocks one timed launch computes (2: fused pair)
     // chunked host -> device pipeline of qrm_detect_host, created on first use: one stream per role
     // (upload, kernels, download) and a ring of staging buffers with the events that hand them on
     struct Stage {
@@ -308,8 +309,8 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         int cur = 0, tcur = 0, in_slots = pf.slots * pf.sub;
         const int blocks = n_run > 0 ? n_run : c->n_blocks; // blocks to run: the first one and C -> C layers m = b - 1
         // Fused schedule when the tile is a single column block: [first + layer 0], (1,2), (3,4), ..; what is
-        // left over runs alone.  While timing is on, the launches of the dominant kind (fused C -> C pairs if
-        // any run, else single C -> C layers) are bracketed by events.
+        // left over runs alone.  While timing is on, the launches of the dominant kind (fused pairs of C -> C
+        // layers that write activations, if any run, else single C -> C layers) are bracketed by events.
         static const bool no_pairs = getenv("QRM_DISABLE_PAIRS") != nullptr; // A/B switch for measurements
         const bool fused = !no_pairs && c->pairable && conv_pair_supported(c->C, g) && blocks >= 2;
         const bool time_pairs = fused && blocks >= 4;
@@ -328,7 +329,7 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         while (b < blocks) {
             const int m = b - 1;
             const bool pair = fused && (m & 1) == 1 && b + 1 < blocks;
-            const bool timed = c->profile && pair == time_pairs;
+            const bool timed = c->profile && pair == time_pairs && !(pair && time_pairs && is_last(b + 1) && blocks >= 6);
             hipEvent_t ev1 = nullptr;
             if (timed) {
                 if (c->ev_used + 2 > c->ev_pool.size()) {
@@ -360,6 +361,7 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
             if (timed) {
                 (void)hipEventRecord(ev1, s);
                 c->prof_flops += (pair ? 2.0 : 1.0) * 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
+                c->prof_blocks = pair ? 2 : 1;
             }
             cur ^= 1;
             tcur ^= 1;
@@ -584,7 +586,7 @@ qrm_status qrm_profile_enable(qrm_ctx *c, int32_t on)
     return QRM_OK;
 }
 
-qrm_status qrm_profile_read(qrm_ctx *c, double *ms_total, int64_t *launches, double *flops)
+qrm_status qrm_profile_read(qrm_ctx *c, double *ms_total, int64_t *launches, double *flops, int32_t *blocks_per_launch)
 {
     if (!c) return QRM_E_INVALID;
     double ms = 0.0;
@@ -598,6 +600,7 @@ qrm_status qrm_profile_read(qrm_ctx *c, double *ms_total, int64_t *launches, dou
     if (ms_total) *ms_total = ms;
     if (launches) *launches = (int64_t)(c->ev_used / 2);
     if (flops) *flops = c->prof_flops;
+    if (blocks_per_launch) *blocks_per_launch = c->prof_blocks;
     c->ev_used = 0;
     c->prof_flops = 0.0;
     return QRM_OK;
