@@ -685,6 +685,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     __shared__ __attribute__((aligned(16))) float s_stat[4][NQ][32];
     __shared__ __attribute__((aligned(16))) float s_mean[4][C];
     __shared__ float s_cnt[4];
+    // FIRST: group B hands its fp32 accumulators to group A, which has time to spare, for the epilogue:
+    // [buffer = row pair parity][wavefront][row * 4 + channel quad][lane] x 4 floats
+    __shared__ __attribute__((aligned(16))) float s_accx[FIRST ? 2 * 4 * 8 * 256 : 4];
+    constexpr int kFinishGroup = FIRST ? 0 : 1; // the group that finishes output rows (stores, statistics)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -793,13 +797,15 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     };
 
     // ---- once per workgroup: biases, the halo columns of the intermediate ring, statistics
-    if (grp == 1) {
-        if (tid - 256 < C) s_biasB[tid - 256] = biasB[tid - 256];
+    if (grp == kFinishGroup) {
         if (lane < 32) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) s_stat[w4][q][lane] = 0.f;
         }
         if (lane == 0) s_cnt[w4] = 0.f;
+    }
+    if (grp == 1) {
+        if (tid - 256 < C) s_biasB[tid - 256] = biasB[tid - 256];
     } else if (FIRST) {
         if (tid < C) s_initA[tid] = biasA[tid];
         for (int i = tid; i < kPairRing * kHaloW; i += 256) s_pix[i / kHaloW][i % kHaloW][3] = 0; // the padding channel
@@ -841,6 +847,39 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         __builtin_amdgcn_s_waitcnt(kWaitVm0);
         __syncthreads();
 
+        // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 held in `a`
+        auto finish = [&](const f32x16 (&a)[RW], int j) {
+            const int ln = pin_in_loop(tid & 63);
+            const int pxl = ln & 31, hf = ln >> 5;
+            const int x = xb * 32 + pxl;
+            const float *si = &s_biasB[cb * 32 + hf * 16];
+            if (!LASTB) {
+                const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+                const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
+#pragma unroll
+                for (int hq = 0; hq < 2; ++hq) {
+                    const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        u32x4 pk;
+                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
+                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
+                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
+                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                        bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                        if (full) *(u32x4 *)dst = pk;
+                        else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                    }
+                }
+            }
+            if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
+                strip_statistics<RW, LASTB>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
+                if (cb == 0 && ln == 0) {
+                    const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
+                    s_cnt[w4] += (float)(rows * cols);
+                }
+            }
+        };
 #pragma unroll 1
         for (int s = 0; s <= S + 2; ++s) {
             if (grp == 0) {
@@ -916,6 +955,19 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                             *(u32x4 *)(ring_mid + slot_of(2 * s + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
                                 (u32x4){0u, 0u, 0u, 0u};
                 }
+                if (FIRST && s >= 3 && s - 3 < S) { // the rows group B accumulated in the previous step
+                    const int j = s - 3;
+                    const float *srcx = &s_accx[(((j & 1) * 4 + w4) * 8) * 256 + ln * 4];
+                    f32x16 a[RW];
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const f32x4 v = *(const f32x4 *)(srcx + (r * 4 + q) * 256);
+                            a[r][4 * q] = v[0]; a[r][4 * q + 1] = v[1]; a[r][4 * q + 2] = v[2]; a[r][4 * q + 3] = v[3];
+                        }
+                    finish(a, j);
+                }
                 if (FIRST && 2 * s + 3 <= 2 * S) { // their slots were last read two steps ago
 #pragma unroll
                     for (int k = 0; k < 2; ++k) pixel_store(2 * s + 3, tid + 256 * k, pv[k], pin[k]);
@@ -924,42 +976,21 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 const int ln = pin_in_loop(tid & 63);
                 const int pxl = ln & 31, hf = ln >> 5;
                 const int x = xb * 32 + pxl;
-                if (s >= 3 && s - 3 < S) { // epilogue of the rows accumulated in the previous step
-                    const int j = s - 3;
-                    const float *si = &s_biasB[cb * 32 + hf * 16];
-                    if (!LASTB) {
-                        const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
-                        const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
-#pragma unroll
-                        for (int hq = 0; hq < 2; ++hq) {
-                            const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
-#pragma unroll
-                            for (int r = 0; r < RW; ++r) {
-                                u32x4 pk;
-                                pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
-                                pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
-                                pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
-                                pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
-                                bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
-                                if (full) *(u32x4 *)dst = pk;
-                                else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
-                            }
-                        }
-                    }
-                    if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
-                        strip_statistics<RW, LASTB>(acc, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
-                        if (cb == 0 && ln == 0) {
-                            const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
-                            s_cnt[w4] += (float)(rows * cols);
-                        }
-                    }
-                }
+                if (!FIRST && s >= 3 && s - 3 < S) finish(acc, s - 3); // the rows accumulated in the previous step
                 if (s >= 2 && s - 2 < S) {
                     const int j = s - 2;
                     lrow_t rowp[RW + 2];
 #pragma unroll
                     for (int r = 0; r < RW + 2; ++r) rowp[r] = mid_base + (uint32_t)slot_of(2 * j - 1 + r) * ROWB;
                     strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                    if (FIRST) { // group A finishes these rows in the next step
+                        float *dst = &s_accx[(((j & 1) * 4 + w4) * 8) * 256 + ln * 4];
+#pragma unroll
+                        for (int r = 0; r < RW; ++r)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+                                *(f32x4 *)(dst + (r * 4 + q) * 256) = (f32x4){acc[r][4 * q], acc[r][4 * q + 1], acc[r][4 * q + 2], acc[r][4 * q + 3]};
+                    }
                 }
             }
             // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
@@ -972,7 +1003,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             lds_barrier();
         }
         // ---- this image's channel sums -> its records; accumulators cleared
-        if (grp == 1 && st.tout) {
+        if (grp == kFinishGroup && st.tout) {
             const int ln = pin_in_loop(tid & 63);
             float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, NQ);
             if (ln < 32) {
