@@ -143,7 +143,7 @@ def small_weights(C, nb, nbits, seed):
 
 
 @pytest.mark.parametrize("C,nb,h,w", [(32, 3, 32, 32), (64, 3, 16, 64), (64, 2, 21, 70), (32, 2, 9, 33),
-                                      (64, 2, 4, 130)])
+                                      (64, 2, 4, 130), (64, 5, 11, 40), (64, 4, 6, 64)])
 def test_extractor_blocks_match_oracle_layer_by_layer(qrm, C, nb, h, w):
     wts = small_weights(C, nb, 16, C + nb)
     rng = np.random.default_rng(h * w)
@@ -175,6 +175,12 @@ EXT_CASES = [
     ("ragged 48x80 c64 b3 48bit", 64, 3, 48, 48, 80, 5),
     ("ragged 30x30 c32 b2 60bit", 32, 2, 60, 30, 30, 9),
     ("tiny 5x7 c64 b2 8bit", 64, 2, 8, 5, 7, 3),
+    # the fused kernels (64 channels, tiles up to 64 wide) on ragged tiles: pair of C -> C blocks followed by a
+    # single last block; last block as the second half of a pair with an odd height; more images than CUs
+    ("ragged 23x50 c64 b5 48bit", 64, 5, 48, 23, 50, 3),
+    ("ragged 37x64 c64 b6 48bit", 64, 6, 48, 37, 64, 2),
+    ("one row 1x64 c64 b4 16bit", 64, 4, 16, 1, 64, 2),
+    ("many images 8x16 c64 b4 24bit", 64, 4, 24, 8, 16, 300),
 ]
 
 
