@@ -838,9 +838,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     }
             }
         } else {
-            if (grp == 0) prepare_init(n);
 #pragma unroll 1
-            for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y);
+            for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y); // first, so that they travel while the correction is computed
+            if (grp == 0) prepare_init(n);
         }
         if (grp == 1)
             for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
