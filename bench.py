@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
 # copy kernel of known size (profiles/conv_pair_c2_hbm_traffic.txt), for the fused pair of C -> C blocks at the
 # default micro-batch of 256 images: 129.57 MiB read + 128.14 MiB written; algorithmic 2 x 128 MiB.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 270228282
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 270228080
 
 
 def main() -> int:
@@ -151,7 +151,20 @@ def main() -> int:
     e2 = torch.empty((n_cw,), dtype=torch.int8, device="cuda")
     t_rs = timed(lambda: ctx.qrm_rs_decode(sym, n_cw, m2, c2, e2, stream=stream))
     rs_bytes = n_cw * (2 * cfg.n + cfg.k + 1)
+    # key verification: on stored messages (streaming, k + 5 bytes per word) and inside the decoder's epilogue
+    n_vw = 1 << 24
+    vmsg = torch.randint(0, 1 << cfg.m, (n_vw, cfg.k), dtype=torch.uint8, device="cuda")
+    vmat = torch.empty((n_vw,), dtype=torch.int32, device="cuda")
+    vdet = torch.empty((n_vw,), dtype=torch.uint8, device="cuda")
+    ctx.qrm_set_key(np.arange(cfg.k, dtype=np.uint8) & ((1 << cfg.m) - 1),
+                    q.binding.qrm_key_threshold(cfg.k * cfg.m, 1e-6))
+    t_vk = timed(lambda: ctx.qrm_verify_key(vmsg, n_vw, vmat, vdet, stream=stream))
+    vk_bytes = n_vw * (cfg.k + 5)
+    del vmsg, vmat, vdet
     stages = {
+        "verify_key": {"us": round(t_vk * 1e6, 2), "words_per_s": round(n_vw / t_vk, 0),
+                       "algorithmic_GBs": round(vk_bytes / t_vk / 1e9, 1),
+                       "frac_hbm": round(vk_bytes / t_vk / 1e9 / PEAK_HBM_GBS, 4), "words": n_vw},
         "tile_crop": {"us": round(t_tile * 1e6, 2), "algorithmic_GBs": round(tile_bytes / t_tile / 1e9, 1),
                       "frac_hbm": round(tile_bytes / t_tile / 1e9 / PEAK_HBM_GBS, 4), "images": N},
         "rs_decode": {"us": round(t_rs * 1e6, 2), "codewords_per_s": round(n_cw / t_rs, 0),

@@ -174,6 +174,39 @@ QRM_API qrm_status qrm_detect(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, 
                       uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
 
 /*
+ * Key verification (Section 4.3: the RS-corrected message is compared with the predetermined key;
+ * Listing 1, `verify(recovered_key, secret_key)`; Table 2: the false-positive rate is held at 1e-6).
+ * An image that carries no watermark yields message bits that agree with the key like fair coin
+ * flips, so the number of agreeing bits among the K = k*m message bits is Binomial(K, 1/2).
+ *
+ * qrm_key_threshold: host-only, no context.  Returns the smallest tau in 0..n_bits+1 with
+ * P(Binomial(n_bits, 1/2) >= tau) <= fpr (n_bits+1 means that no image can pass), or -1 for
+ * n_bits outside 1..2040 or fpr negative / NaN.  For 48 bits and 1e-6 it returns 41.
+ *
+ * qrm_set_key: h_key HOST u8 [k], one m-bit symbol per byte in the message's order (bits above m are
+ * ignored); tau as above.  Copies the key to the device synchronously; must not be called while calls
+ * that verify are still running on any stream.  Errors: QRM_E_INVALID (no code in ctx, NULL, tau
+ * outside 0..k*m+1).
+ *
+ * qrm_verify_key: d_msg u8 [N,k] (e.g. the output of qrm_rs_decode) -> d_matches i32 [N] = number
+ * of message bits equal to the key's (k*m for the key itself); d_detected u8 [N] = (matches >= tau),
+ * may be NULL.  A word whose decoding failed is judged on its uncorrected message symbols.
+ * Errors: QRM_E_INVALID (no key set, NULL pointer, N < 0).
+ *
+ * qrm_detect_verify: qrm_detect with the comparison done in the decoder's epilogue; arguments as
+ * qrm_detect plus d_matches (required) and d_detected (may be NULL).
+ */
+QRM_API int32_t qrm_key_threshold(int32_t n_bits, double fpr);
+QRM_API qrm_status qrm_set_key(qrm_ctx *ctx, const uint8_t *h_key, int32_t tau);
+QRM_API qrm_status qrm_verify_key(qrm_ctx *ctx, const uint8_t *d_msg, int64_t N, int32_t *d_matches,
+                                  uint8_t *d_detected, void *stream);
+QRM_API qrm_status qrm_detect_verify(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                                     const int32_t *d_off_yx, int32_t tile,
+                                     float *d_logits, uint8_t *d_bits,
+                                     uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr,
+                                     int32_t *d_matches, uint8_t *d_detected, void *stream);
+
+/*
  * The same path for a batch that lives in HOST memory, streamed through the GPU in chunks (the
  * pipelined detection of Section 5: the transfer of one mini-batch overlaps the kernels of another;
  * Section 7 streams up to a million images this way).  The context owns three (default-priority)

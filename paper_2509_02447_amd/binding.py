@@ -39,7 +39,8 @@ class _RsDesc(C.Structure):
 
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
-           "qrm_detect_host", "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
+           "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
+           "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
 
 
 def lib_path() -> str:
@@ -78,6 +79,14 @@ def load_library():
     lib.qrm_detect.restype = C.c_int
     lib.qrm_detect_host.argtypes = [vp, C.POINTER(vp), i32, i32, i32, i32, C.POINTER(vp), i32, i32, vp, vp, vp]
     lib.qrm_detect_host.restype = C.c_int
+    lib.qrm_key_threshold.argtypes = [i32, C.c_double]
+    lib.qrm_key_threshold.restype = C.c_int32
+    lib.qrm_set_key.argtypes = [vp, vp, i32]
+    lib.qrm_set_key.restype = C.c_int
+    lib.qrm_verify_key.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.qrm_verify_key.restype = C.c_int
+    lib.qrm_detect_verify.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.qrm_detect_verify.restype = C.c_int
     lib.qrm_profile_enable.argtypes = [vp, i32]
     lib.qrm_profile_enable.restype = C.c_int
     lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
@@ -91,6 +100,10 @@ def load_library():
 
 def version() -> str:
     return load_library().qrm_version().decode()
+
+
+def qrm_key_threshold(n_bits: int, fpr: float) -> int:
+    return int(load_library().qrm_key_threshold(int(n_bits), float(fpr)))
 
 
 def _fptr(a: Optional[np.ndarray]):
@@ -234,3 +247,19 @@ class Context:
             offs = (C.c_void_p * max(1, n))(*[_hptr(t) for t in h_off_chunks])
         self._check(self._lib.qrm_detect_host(self._h, chunks, int(n), int(chunk_images), int(H), int(W), offs, int(tile),
                                               int(depth), _hptr(h_msg), _hptr(h_codeword), _hptr(h_nerr)))
+
+    def qrm_set_key(self, h_key, tau: int):
+        key = np.ascontiguousarray(h_key, dtype=np.uint8).reshape(-1)
+        assert key.size == self.k, "the key has k symbols"
+        self._check(self._lib.qrm_set_key(self._h, key.ctypes.data, int(tau)))
+
+    def qrm_verify_key(self, d_msg, N, d_matches, d_detected=None, stream=None):
+        self._check(self._lib.qrm_verify_key(self._h, _dptr(d_msg), int(N), _dptr(d_matches), _dptr(d_detected),
+                                             _stream_handle(stream)))
+
+    def qrm_detect_verify(self, d_images, N, H, W, d_off_yx, tile, d_logits, d_bits, d_msg, d_codeword, d_nerr,
+                          d_matches, d_detected=None, stream=None):
+        self._check(self._lib.qrm_detect_verify(self._h, _dptr(d_images), int(N), int(H), int(W), _dptr(d_off_yx),
+                                                int(tile), _dptr(d_logits), _dptr(d_bits), _dptr(d_msg),
+                                                _dptr(d_codeword), _dptr(d_nerr), _dptr(d_matches), _dptr(d_detected),
+                                                _stream_handle(stream)))

@@ -65,7 +65,9 @@ struct qrm_ctx {
     bool pairable = false;                // weights are prepared for the fused schedule (see qrm_create)
     // code
     RsParams rs{};
-    void *d_tables = nullptr;
+    void *d_tables = nullptr;             // 1 KiB: antilog table, log table at 512, key symbols at 768
+    bool has_key = false;
+    int key_tau = 0;
     // workspace
     int micro_batch = 0; // 0 = default
     Slot slots[QRM_MAX_STREAMS + 1]; // the caller's streams plus the kernel stream of qrm_detect_host
@@ -90,6 +92,69 @@ struct qrm_ctx {
 };
 
 namespace {
+
+// Non-negative integers of a few thousand bits, just enough for exact binomial tails.
+struct Big {
+    std::vector<uint32_t> w; // little endian, no leading zero words
+    explicit Big(uint64_t v = 0)
+    {
+        if (v & 0xffffffffu || v >> 32) w.push_back((uint32_t)v);
+        if (v >> 32) w.push_back((uint32_t)(v >> 32));
+    }
+    void trim() { while (!w.empty() && w.back() == 0) w.pop_back(); }
+    void add(const Big &o)
+    {
+        if (w.size() < o.w.size()) w.resize(o.w.size(), 0);
+        uint64_t carry = 0;
+        for (size_t i = 0; i < w.size(); ++i) {
+            carry += (uint64_t)w[i] + (i < o.w.size() ? o.w[i] : 0u);
+            w[i] = (uint32_t)carry;
+            carry >>= 32;
+        }
+        if (carry) w.push_back((uint32_t)carry);
+    }
+    void mul_small(uint32_t f)
+    {
+        uint64_t carry = 0;
+        for (auto &x : w) {
+            carry += (uint64_t)x * f;
+            x = (uint32_t)carry;
+            carry >>= 32;
+        }
+        if (carry) w.push_back((uint32_t)carry);
+        trim();
+    }
+    void div_small(uint32_t d) // the remainder is dropped (callers divide exactly)
+    {
+        uint64_t rem = 0;
+        for (size_t i = w.size(); i-- > 0;) {
+            const uint64_t cur = (rem << 32) | w[i];
+            w[i] = (uint32_t)(cur / d);
+            rem = cur % d;
+        }
+        trim();
+    }
+    void shl(int bits)
+    {
+        if (w.empty() || bits <= 0) return;
+        const int words = bits / 32, r = bits % 32;
+        std::vector<uint32_t> o(w.size() + words + 1, 0);
+        for (size_t i = 0; i < w.size(); ++i) {
+            const uint64_t v = (uint64_t)w[i] << r;
+            o[i + words] |= (uint32_t)v;
+            o[i + words + 1] |= (uint32_t)(v >> 32);
+        }
+        w.swap(o);
+        trim();
+    }
+    int cmp(const Big &o) const
+    {
+        if (w.size() != o.w.size()) return w.size() < o.w.size() ? -1 : 1;
+        for (size_t i = w.size(); i-- > 0;)
+            if (w[i] != o.w[i]) return w[i] < o.w[i] ? -1 : 1;
+        return 0;
+    }
+};
 
 qrm_status fail(qrm_ctx *c, qrm_status st, const std::string &msg)
 {
@@ -681,17 +746,82 @@ qrm_status qrm_rs_decode(qrm_ctx *c, const uint8_t *d_symbols, int64_t N, uint8_
     if (!d_symbols || !d_msg || !d_nerr) return fail(c, QRM_E_INVALID, "d_symbols / d_msg / d_nerr is NULL");
     hipError_t e = hipSetDevice(c->device);
     if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
-    e = launch_rs_decode(c->rs, d_symbols, N, d_msg, d_codeword, d_nerr, (hipStream_t)stream);
+    e = launch_rs_decode(c->rs, d_symbols, N, d_msg, d_codeword, d_nerr, KeyArgs{}, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
     return QRM_OK;
 }
 
-qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W, const int32_t *d_off_yx,
-                      int32_t tile, float *d_logits, uint8_t *d_bits, uint8_t *d_msg, uint8_t *d_codeword,
-                      int8_t *d_nerr, void *stream)
+int32_t qrm_key_threshold(int32_t n_bits, double fpr)
+{
+    if (n_bits < 1 || n_bits > 8 * 255 || !(fpr >= 0.0)) return -1;
+    // Exact integer arithmetic: P(X >= tau) <= fpr  <=>  sum_{j >= tau} C(K,j) <= fpr * 2^K, and a double
+    // is an integer times a power of two, so both sides are integers (after a common shift).
+    const int K = n_bits;
+    if (fpr >= 1.0) return 0;
+    if (fpr == 0.0) return K + 1;
+    int e2 = 0;
+    const double fr = frexp(fpr, &e2);                       // fpr = fr * 2^e2, 0.5 <= fr < 1
+    const uint64_t mant = (uint64_t)ldexp(fr, 53);           // fpr = mant * 2^(e2-53)
+    const int sh = K + e2 - 53;                              // fpr * 2^K = mant * 2^sh
+    Big rhs(mant), tail(0), term(1);                         // term = C(K,K)
+    if (sh >= 0) rhs.shl(sh);
+    int tau = K + 1;
+    for (int j = K; j >= 0; --j) {
+        tail.add(term);
+        Big lhs = tail;
+        if (sh < 0) lhs.shl(-sh);
+        if (lhs.cmp(rhs) > 0) break;
+        tau = j;
+        term.mul_small((uint32_t)j);                         // C(K,j-1) = C(K,j) * j / (K-j+1), exactly
+        term.div_small((uint32_t)(K - j + 1));
+    }
+    return tau;
+}
+
+qrm_status qrm_set_key(qrm_ctx *c, const uint8_t *h_key, int32_t tau)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_rs) return fail(c, QRM_E_INVALID, "context has no Reed-Solomon code");
+    if (!h_key) return fail(c, QRM_E_INVALID, "h_key is NULL");
+    if (tau < 0 || tau > c->rs.k * c->rs.m + 1) return fail(c, QRM_E_INVALID, "tau outside 0 .. k*m+1");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    uint8_t masked[256] = {0};
+    for (int i = 0; i < c->rs.k; ++i) masked[i] = (uint8_t)(h_key[i] & (c->rs.q - 1));
+    e = hipMemcpy((uint8_t *)c->d_tables + 768, masked, 256, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(c, e, "hipMemcpy(key)");
+    c->has_key = true;
+    c->key_tau = tau;
+    return QRM_OK;
+}
+
+qrm_status qrm_verify_key(qrm_ctx *c, const uint8_t *d_msg, int64_t N, int32_t *d_matches, uint8_t *d_detected,
+                          void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (!c->has_rs || !c->has_key) return fail(c, QRM_E_INVALID, "context has no code or no key (qrm_set_key)");
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (N == 0) return QRM_OK;
+    if (!d_msg || !d_matches) return fail(c, QRM_E_INVALID, "d_msg / d_matches is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    const KeyArgs key{(const uint8_t *)c->d_tables + 768, c->key_tau, d_matches, d_detected};
+    e = launch_verify(c->rs, d_msg, N, key, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(c, e, "verify launch");
+    return QRM_OK;
+}
+
+} // extern "C"
+
+static qrm_status detect_common(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                                const int32_t *d_off_yx, int32_t tile, float *d_logits, uint8_t *d_bits,
+                                uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, bool verify, int32_t *d_matches,
+                                uint8_t *d_detected, void *stream)
 {
     if (!c) return QRM_E_INVALID;
     if (!c->has_ext || !c->has_rs) return fail(c, QRM_E_INVALID, "context needs both an extractor and a code");
+    if (verify && !c->has_key) return fail(c, QRM_E_INVALID, "context has no key (qrm_set_key)");
+    if (verify && N > 0 && !d_matches) return fail(c, QRM_E_INVALID, "d_matches is NULL");
     if (c->n_bits != c->rs.n * c->rs.m) return fail(c, QRM_E_INVALID, "n_bits != n * m");
     if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
     if (tile <= 0 || H <= 0 || W <= 0 || tile > H || tile > W || H > 16384 || W > 16384)
@@ -710,9 +840,30 @@ qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H,
                 {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
     st = run_extractor(c, slot, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, s);
     if (st != QRM_OK) return st;
-    e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, s);
+    KeyArgs key{};
+    if (verify) key = KeyArgs{(const uint8_t *)c->d_tables + 768, c->key_tau, d_matches, d_detected};
+    e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, key, s);
     if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
     return QRM_OK;
+}
+
+extern "C" {
+
+qrm_status qrm_detect(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W, const int32_t *d_off_yx,
+                      int32_t tile, float *d_logits, uint8_t *d_bits, uint8_t *d_msg, uint8_t *d_codeword,
+                      int8_t *d_nerr, void *stream)
+{
+    return detect_common(c, d_images, N, H, W, d_off_yx, tile, d_logits, d_bits, d_msg, d_codeword, d_nerr, false,
+                         nullptr, nullptr, stream);
+}
+
+qrm_status qrm_detect_verify(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                             const int32_t *d_off_yx, int32_t tile, float *d_logits, uint8_t *d_bits, uint8_t *d_msg,
+                             uint8_t *d_codeword, int8_t *d_nerr, int32_t *d_matches, uint8_t *d_detected,
+                             void *stream)
+{
+    return detect_common(c, d_images, N, H, W, d_off_yx, tile, d_logits, d_bits, d_msg, d_codeword, d_nerr, true,
+                         d_matches, d_detected, stream);
 }
 
 // Grows *p to at least `need` bytes (contents are not kept).

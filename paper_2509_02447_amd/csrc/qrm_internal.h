@@ -109,8 +109,18 @@ struct RsParams {
     const uint8_t *log;  // device, [q], log[0] unused
 };
 
+// Key verification: `key` device [k] symbols; matches null = no verification.
+struct KeyArgs {
+    const uint8_t *key = nullptr;
+    int tau = 0;
+    int32_t *matches = nullptr; // [N] number of message bits equal to the key's
+    uint8_t *detected = nullptr; // [N] matches >= tau, or null
+};
+
 hipError_t launch_rs_decode(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
-                            hipStream_t s);
+                            const KeyArgs &key, hipStream_t s);
+// matches / detected for messages already in memory (msg device [N,k])
+hipError_t launch_verify(const RsParams &p, const uint8_t *msg, int64_t N, const KeyArgs &key, hipStream_t s);
 
 // host-side helpers
 uint16_t f32_to_bf16_rne(float f);

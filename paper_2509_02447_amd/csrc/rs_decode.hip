@@ -11,6 +11,11 @@
 // four per 32-bit word), the short serial Berlekamp-Massey recursion is replicated in every lane, and
 // Chien search and Forney run one position per lane.  Log / antilog tables live in LDS.  No lane ever
 // leaves the main path early, so cross-lane operations always see a full wavefront.
+//
+// Key verification (Section 4.3: the corrected message is compared with the predetermined key) rides in
+// the decoder's epilogue when a key is given: every lane counts the bits of its message symbol that
+// agree with the key's, the group adds the counts, lane 0 writes the count and (count >= tau).  The
+// same count for messages already in memory is `verify_kernel`, a plain streaming pass.
 #include "qrm_internal.h"
 
 namespace qrm {
@@ -44,17 +49,28 @@ __device__ __forceinline__ int group_count(bool pred, int lane)
     return __popcll((mask >> sh) & ((1ull << G) - 1ull));
 }
 
+template <int G>
+__device__ __forceinline__ int group_add(int v)
+{
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, G);
+    return v;
+}
+
 template <int G, int TMAX, int SPL>
 __global__ __launch_bounds__(256) void rs_decode_kernel(RsParams p, const uint8_t *__restrict__ sym, int64_t N,
                                                         uint8_t *__restrict__ msg, uint8_t *__restrict__ cw,
-                                                        int8_t *__restrict__ nerr)
+                                                        int8_t *__restrict__ nerr, KeyArgs key)
 {
     __shared__ uint8_t s_exp[512];
     __shared__ uint8_t s_log[256];
+    __shared__ uint8_t s_key[256];
     const int tid = threadIdx.x;
     const int ord = p.q - 1;
+    const bool with_key = key.matches != nullptr; // the same for every lane
     for (int i = tid; i < 2 * ord; i += 256) s_exp[i] = p.exp2[i];
     for (int i = tid; i < p.q; i += 256) s_log[i] = p.log[i];
+    s_key[tid] = (with_key && tid < p.k) ? key.key[tid] : 0;
     __syncthreads();
     Gf gf{s_exp, s_log, ord};
 
@@ -201,51 +217,102 @@ __global__ __launch_bounds__(256) void rs_decode_kernel(RsParams p, const uint8_
         if (group_count<G>(bad, tid) != 0) fail = true;
 
         // ---- write back
+        int agree = 0;
 #pragma unroll
         for (int s = 0; s < SPL; ++s) {
             const int i = lane_g + s * G;
             if (valid && i < n) {
                 const uint8_t out = (uint8_t)(fail ? r[s] : (r[s] ^ ev[s]));
                 if (cw) cw[w * n + i] = out;
-                if (i < k) msg[w * k + i] = out;
+                if (i < k) {
+                    msg[w * k + i] = out;
+                    agree += p.m - __popc((unsigned)(out ^ s_key[i]) & (unsigned)(p.q - 1));
+                }
             }
         }
         if (valid && lane_g == 0) nerr[w] = (int8_t)(fail ? -1 : L);
+        if (with_key) {
+            agree = group_add<G>(agree);
+            if (valid && lane_g == 0) {
+                key.matches[w] = agree;
+                if (key.detected) key.detected[w] = (uint8_t)(agree >= key.tau);
+            }
+        }
+    }
+}
+
+// Agreement of stored messages with the key: one word per lane, V bytes of it per load.
+template <typename V>
+__global__ __launch_bounds__(256) void verify_kernel(const uint8_t *__restrict__ msg, int64_t N, int k, int m,
+                                                     KeyArgs key)
+{
+    __shared__ V s_key[256 / sizeof(V)];
+    const int per = k / (int)sizeof(V);
+    if ((int)threadIdx.x < per) s_key[threadIdx.x] = reinterpret_cast<const V *>(key.key)[threadIdx.x];
+    __syncthreads();
+    V mask = 0;
+#pragma unroll
+    for (int b = 0; b < (int)sizeof(V); ++b) mask |= (V)((1u << m) - 1u) << (8 * b);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x; w < N; w += stride) {
+        const V *src = reinterpret_cast<const V *>(msg + w * k);
+        int differ = 0;
+        for (int j = 0; j < per; ++j) differ += __popcll((unsigned long long)((src[j] ^ s_key[j]) & mask));
+        const int agree = k * m - differ;
+        key.matches[w] = agree;
+        if (key.detected) key.detected[w] = (uint8_t)(agree >= key.tau);
     }
 }
 
 template <int G, int TMAX, int SPL>
 hipError_t launch_one(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
-                      hipStream_t s)
+                      const KeyArgs &key, hipStream_t s)
 {
     constexpr int GPB = 256 / G;
     int64_t blocks = (N + GPB - 1) / GPB;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL((rs_decode_kernel<G, TMAX, SPL>), dim3((unsigned)blocks), dim3(256), 0, s, p, sym, N, msg, cw,
-                       nerr);
+                       nerr, key);
     return hipGetLastError();
 }
 
 template <int TMAX>
 hipError_t launch_t(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
-                    hipStream_t s)
+                    const KeyArgs &key, hipStream_t s)
 {
-    if (p.n <= 16) return launch_one<16, TMAX, 1>(p, sym, N, msg, cw, nerr, s);
-    if (p.n <= 64) return launch_one<64, TMAX, 1>(p, sym, N, msg, cw, nerr, s);
-    if (p.n <= 128) return launch_one<64, TMAX, 2>(p, sym, N, msg, cw, nerr, s);
-    return launch_one<64, TMAX, 4>(p, sym, N, msg, cw, nerr, s);
+    if (p.n <= 16) return launch_one<16, TMAX, 1>(p, sym, N, msg, cw, nerr, key, s);
+    if (p.n <= 64) return launch_one<64, TMAX, 1>(p, sym, N, msg, cw, nerr, key, s);
+    if (p.n <= 128) return launch_one<64, TMAX, 2>(p, sym, N, msg, cw, nerr, key, s);
+    return launch_one<64, TMAX, 4>(p, sym, N, msg, cw, nerr, key, s);
 }
 
 } // namespace
 
 hipError_t launch_rs_decode(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
-                            hipStream_t s)
+                            const KeyArgs &key, hipStream_t s)
 {
     if (N <= 0) return hipSuccess;
     const int t = p.two_t / 2;
-    if (t <= 2) return launch_t<2>(p, sym, N, msg, cw, nerr, s);
-    if (t <= 4) return launch_t<4>(p, sym, N, msg, cw, nerr, s);
-    return launch_t<8>(p, sym, N, msg, cw, nerr, s);
+    if (t <= 2) return launch_t<2>(p, sym, N, msg, cw, nerr, key, s);
+    if (t <= 4) return launch_t<4>(p, sym, N, msg, cw, nerr, key, s);
+    return launch_t<8>(p, sym, N, msg, cw, nerr, key, s);
+}
+
+hipError_t launch_verify(const RsParams &p, const uint8_t *msg, int64_t N, const KeyArgs &key, hipStream_t s)
+{
+    if (N <= 0) return hipSuccess;
+    int64_t blocks = (N + 255) / 256;
+    if (blocks > 16384) blocks = 16384;
+    const dim3 grid((unsigned)blocks), block(256);
+    // wide loads need every word (and the key) to start on a multiple of the load width
+    const uintptr_t a = (uintptr_t)msg | (uintptr_t)key.key;
+    if (p.k % 8 == 0 && a % 8 == 0)
+        hipLaunchKernelGGL(verify_kernel<uint64_t>, grid, block, 0, s, msg, N, p.k, p.m, key);
+    else if (p.k % 4 == 0 && a % 4 == 0)
+        hipLaunchKernelGGL(verify_kernel<uint32_t>, grid, block, 0, s, msg, N, p.k, p.m, key);
+    else
+        hipLaunchKernelGGL(verify_kernel<uint8_t>, grid, block, 0, s, msg, N, p.k, p.m, key);
+    return hipGetLastError();
 }
 
 } // namespace qrm

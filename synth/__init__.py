@@ -184,3 +184,29 @@ def random_words(cfg_index: int, count: int, n: int, m: int, block: int = 1000) 
     """Uniformly random received words u8 [count,n] (symbols < 2^m)."""
     g = _rng(cfg_index, _T_RS, block)
     return g.integers(0, 1 << m, size=(count, n), dtype=np.uint8)
+
+
+def key_cases(cfg_index: int, count: int, k: int, m: int, block: int = 2000) -> Tuple[np.ndarray, np.ndarray]:
+    """A secret key and recovered messages to hold against it.
+
+    Returns (key u8 [k], msgs u8 [count,k]).  A third of the messages are the key with 0..k*m/4 randomly
+    chosen bits flipped (a watermarked image after decoding), the rest are uniform (an image that carries
+    no watermark); message 0 is the key itself.
+    """
+    g = _rng(cfg_index, _T_RS, block)
+    q = 1 << m
+    key = g.integers(0, q, size=k, dtype=np.uint8)
+    msgs = g.integers(0, q, size=(count, k), dtype=np.uint8)
+    marked = g.random(size=count) < 1.0 / 3.0
+    if count:
+        marked[0] = True
+    nflip = g.integers(0, k * m // 4 + 1, size=count)
+    if count:
+        nflip[0] = 0
+    order = np.argsort(g.random(size=(count, k * m)), axis=1)
+    for i in np.nonzero(marked)[0]:
+        w = key.copy()
+        for b in order[i, :nflip[i]]:
+            w[b // m] ^= np.uint8(1 << (b % m))
+        msgs[i] = w
+    return key, msgs

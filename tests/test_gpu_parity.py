@@ -3,6 +3,8 @@
 Bit-exact for tile crops, symbols and Reed-Solomon outputs; extractor logits within
 2e-2 * max(1, |ref|) and hard bits equal wherever |oracle logit| > 1e-2.
 """
+from fractions import Fraction
+
 import numpy as np
 import pytest
 import torch
@@ -381,6 +383,134 @@ def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
 
 
 # ---------------------------------------------------------------- error paths (host side only)
+
+# ---------------------------------------------------------------- key verification
+
+from oracle import keycheck
+
+
+@pytest.mark.parametrize("m,poly,n,k", [(4, 0x13, 12, 8), (8, 0x11D, 12, 8), (4, 0x13, 15, 11), (8, 0x11D, 20, 4),
+                                        (5, 0x25, 31, 27), (8, 0x11D, 255, 239)])
+@pytest.mark.parametrize("N", [1, 257, 70001])
+def test_verify_key_bit_exact(qrm, m, poly, n, k, N):
+    key, msgs = synth.key_cases(1, N, k, m)
+    tau = qrm.binding.qrm_key_threshold(k * m, 1e-6)
+    if k * m <= 256:
+        assert tau == keycheck.key_threshold(k * m, Fraction(1e-6))
+    else:   # the oracle's search is quadratic in the length: check the two tails that define tau instead
+        assert keycheck.binomial_tail(k * m, tau) <= Fraction(1e-6) < keycheck.binomial_tail(k * m, tau - 1)
+    ctx = qrm.Context(rs=dict(m=m, prim_poly=poly, n=n, k=k, fcr=1))
+    ctx.qrm_set_key(key, tau)
+    d_matches, d_det = empty((N,), torch.int32), empty((N,), torch.uint8)
+    ctx.qrm_verify_key(dev(msgs), N, d_matches, d_det)
+    torch.cuda.synchronize()
+    S = min(N, max(50, 200000 // (k * m)))                              # python loops: a sample
+    ref_matches, ref_det = keycheck.verify_key(msgs[:S], key, m, tau)
+    assert np.array_equal(d_matches.cpu().numpy()[:S], ref_matches)
+    assert np.array_equal(d_det.cpu().numpy()[:S], ref_det)
+    # the rest through a property that holds at any size: agreeing bits = k*m - popcount(msg xor key)
+    x = (msgs ^ key[None, :]) & np.uint8((1 << m) - 1)
+    pop = np.unpackbits(x, axis=1).sum(axis=1).astype(np.int32)
+    assert np.array_equal(d_matches.cpu().numpy(), k * m - pop)
+    assert np.array_equal(d_det.cpu().numpy(), (k * m - pop >= tau).astype(np.uint8))
+    assert d_matches[0].item() == k * m and d_det[0].item() == 1
+    # without the flag output, and with high bits set in the stored symbols when m < 8
+    d2 = empty((N,), torch.int32)
+    noisy = msgs | np.uint8((0xFF << m) & 0xFF)
+    ctx.qrm_verify_key(dev(noisy), N, d2, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(d2.cpu().numpy(), k * m - pop)
+    ctx.close()
+
+
+def test_verify_key_unaligned_message_buffer(qrm):
+    m, k, N = 4, 8, 1000
+    key, msgs = synth.key_cases(1, N, k, m, block=2001)
+    ctx = qrm.Context(rs=dict(m=m, prim_poly=0x13, n=12, k=k, fcr=1))
+    ctx.qrm_set_key(key, 30)
+    buf = empty((N * k + 3,), torch.uint8)
+    view = buf[3:]                                   # starts 3 bytes into an allocation: no wide loads
+    view.copy_(dev(msgs).reshape(-1))
+    d_matches, d_det = empty((N,), torch.int32), empty((N,), torch.uint8)
+    ctx._check(ctx._lib.qrm_verify_key(ctx._h, view.data_ptr(), N, d_matches.data_ptr(), d_det.data_ptr(), None))
+    torch.cuda.synchronize()
+    rm, rd = keycheck.verify_key(msgs, key, m, 30)
+    assert np.array_equal(d_matches.cpu().numpy(), rm) and np.array_equal(d_det.cpu().numpy(), rd)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,count", [("C1", 16), ("C2", 96)])
+def test_detect_verify_equals_detect_then_oracle_verification(qrm, name, count):
+    cfg = synth.CONFIGS[name]
+    wts = synth.config_weights(cfg)
+    imgs, off = synth.images(cfg, 0, count), synth.offsets(cfg, 0, count)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    plain = run_detect(ctx, cfg, imgs, off)
+    check_detect(cfg, wts, imgs, off, plain, f"{name} detect before verification")
+    # the key is what image 5 decodes to, with two bits flipped: image 5 must be found, random ones not
+    key = plain["msg"][5].copy()
+    key[0] ^= 1
+    key[cfg.k - 1] ^= 2
+    K = cfg.k * cfg.m
+    tau = qrm.binding.qrm_key_threshold(K, 1e-6)
+    ctx.qrm_set_key(key, tau)
+    N = count
+    d_logits, d_bits = empty((N, cfg.n_bits), torch.float32), empty((N, cfg.n_bits), torch.uint8)
+    d_msg, d_cw, d_ne = empty((N, cfg.k), torch.uint8), empty((N, cfg.n), torch.uint8), empty((N,), torch.int8)
+    d_matches, d_det = empty((N,), torch.int32), empty((N,), torch.uint8)
+    ctx.qrm_detect_verify(dev(imgs), N, cfg.H, cfg.W, dev(off), cfg.tile, d_logits, d_bits, d_msg, d_cw, d_ne,
+                          d_matches, d_det)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_msg.cpu().numpy(), plain["msg"]) and np.array_equal(d_ne.cpu().numpy(), plain["nerr"])
+    assert np.array_equal(d_cw.cpu().numpy(), plain["codeword"]) and np.array_equal(d_bits.cpu().numpy(), plain["bits"])
+    rm, rd = keycheck.verify_key(plain["msg"], key, cfg.m, keycheck.key_threshold(K, Fraction(1e-6)))
+    assert np.array_equal(d_matches.cpu().numpy(), rm) and np.array_equal(d_det.cpu().numpy(), rd)
+    assert rm[5] == K - 2 and rd[5] == 1
+    # lean call: only what a detector needs
+    m2, det2 = empty((N,), torch.int32), empty((N,), torch.uint8)
+    ctx.qrm_detect_verify(dev(imgs), N, cfg.H, cfg.W, dev(off), cfg.tile, None, None, d_msg, None, d_ne, m2, det2)
+    torch.cuda.synchronize()
+    assert np.array_equal(m2.cpu().numpy(), rm) and np.array_equal(det2.cpu().numpy(), rd)
+    ctx.close()
+
+
+def test_rs_decode_long_code_then_key_comparison(qrm):
+    """RS(255,239): four symbols per lane, t = 8; then the comparison with a key on its messages."""
+    m, poly, n, k = 8, 0x11D, 255, 239
+    msgs, err, _ = synth.rs_cases(3, 500, n, k, m, max_err=9, block=7)
+    words = oracle.rs_encode(msgs, m, poly, n, k, 1) ^ err
+    ctx = qrm.Context(rs=dict(m=m, prim_poly=poly, n=n, k=k, fcr=1))
+    gm, gc, ge = gpu_rs_decode(ctx, words)
+    om, oc, oe = oracle.rs_decode(words, m, poly, n, k, 1)
+    assert np.array_equal(gm, om) and np.array_equal(gc, oc) and np.array_equal(ge, oe)
+    key = msgs[3]
+    ctx.qrm_set_key(key, 1700)
+    d_matches, d_det = empty((500,), torch.int32), empty((500,), torch.uint8)
+    ctx.qrm_verify_key(dev(gm), 500, d_matches, d_det)
+    torch.cuda.synchronize()
+    rm, rd = keycheck.verify_key(om, key, m, 1700)
+    assert np.array_equal(d_matches.cpu().numpy(), rm) and np.array_equal(d_det.cpu().numpy(), rd)
+    ctx.close()
+
+
+def test_verification_error_statuses(qrm):
+    cfg = synth.CONFIGS["C1"]
+    ctx = qrm.Context(weights=synth.config_weights(cfg), rs=rs_dict(cfg))
+    d = empty((4,), torch.int32)
+    with pytest.raises(qrm.QrmError):       # no key yet
+        ctx.qrm_verify_key(empty((4, cfg.k), torch.uint8), 4, d, None)
+    with pytest.raises(qrm.QrmError):       # tau out of range
+        ctx.qrm_set_key(np.zeros(cfg.k, np.uint8), cfg.k * cfg.m + 2)
+    ctx.qrm_set_key(np.zeros(cfg.k, np.uint8), 3)
+    with pytest.raises(qrm.QrmError):       # d_matches missing
+        ctx.qrm_verify_key(empty((4, cfg.k), torch.uint8), 4, None, None)
+    ctx.qrm_verify_key(empty((0, cfg.k), torch.uint8), 0, d, None)      # empty batch is fine
+    ext_only = qrm.Context(weights=synth.config_weights(cfg))
+    with pytest.raises(qrm.QrmError):       # no code, hence no key length
+        ext_only._check(ext_only._lib.qrm_set_key(ext_only._h, np.zeros(16, np.uint8).ctypes.data, 3))
+    ext_only.close()
+    ctx.close()
+
 
 def test_error_statuses(qrm):
     cfg = synth.CONFIGS["C2"]
