@@ -642,6 +642,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 //   end : s_waitcnt vmcnt(0) (the loads issued a step ago), then the direct-to-LDS loads of input rows
 //         2s+5 (group A) and 2s+6 (group B), needed in step s+2; one workgroup barrier
 // Row y of either map lives in ring slot (y + 2) mod 8.
+// A workgroup's images follow each other without a gap: see the main loop (virtual rows).
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
 // (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
 // image, so there are no channel means to correct its bias with.
@@ -732,10 +733,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         const int gx = col - 1;
         lane_off[k] = sl >= SLOTS ? kSlotNone : (cpos < C / 8 && gx >= 0 && gx < g.w) ? (uint32_t)((gx * C + cpos * 8) * 2) : kSlotZero;
     }
-    auto issue_row = [&](int n, int y) {
+    auto issue_row = [&](int n, int y, int vrow) { // vrow: the row's place in the stream of images (see the main loop)
         const bool rowok = y >= 0 && y < g.h;
         const uint32_t rowoff = in_off + (uint32_t)n * img_bytes + (uint32_t)(y * g.w * C * 2);
-        uint8_t *dst = ring_in + slot_of(y) * ROWB;
+        uint8_t *dst = ring_in + slot_of(vrow) * ROWB;
 #pragma unroll
         for (int k = 0; k < QPW; ++k) {
             const int q = w4 + 4 * k;
@@ -785,7 +786,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         inside = e < 2 * kRowElems && ty >= 0 && ty < g.h && tx >= 0 && tx < g.w;
         return inside ? tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx] : (uint8_t)0;
     };
-    auto pixel_store = [&](int y0, int e, uint8_t v, bool inside) {
+    auto pixel_store = [&](int y0, int e, uint8_t v, bool inside) { // y0: place of the first row in the stream of images
         if (e < 2 * kRowElems) {
             const int row = e / kRowElems, rem = e - row * kRowElems;
             const int c = rem / kHaloW, col = rem - c * kHaloW;
@@ -816,195 +817,98 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         *(u32x4 *)(ring_mid + row * ROWB + (side ? (kHaloW - 1) : 0) * K::PS + sl * 16) = (u32x4){0u, 0u, 0u, 0u};
     }
 
-    f32x16 acc[RW];
-    for (int n = n_begin; n < n_end; ++n) {
-        // ---- image prologue: correction of this image, input rows -1 .. 4 (FIRST: -1 .. 2), intermediate row -1 = zero
-        const uint8_t *tile0 = nullptr;
-        if (FIRST) {
-            int oy = 0, ox = 0;
-            if (src.off) {
-                oy = clampi(src.off[2 * n], 0, src.H - g.h);
-                ox = clampi(src.off[2 * n + 1], 0, src.W - g.w);
-            }
-            tile0 = src.img + (int64_t)n * 3 * plane + (int64_t)oy * src.W + ox;
-            if (grp == 0) {
-#pragma unroll 1
-                for (int y0 = -1; y0 <= 1; y0 += 2)
-#pragma unroll
-                    for (int k = 0; k < 2; ++k) {
-                        bool inside;
-                        const uint8_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside);
-                        pixel_store(y0, tid + 256 * k, v, inside);
-                    }
-            }
-        } else {
-#pragma unroll 1
-            for (int y = -1 + grp; y <= 4; y += 2) issue_row(n, y); // first, so that they travel while the correction is computed
-            if (grp == 0) prepare_init(n);
+    // The images of a workgroup form one stream of row pairs: image i takes P = S + 1 steps (S row pairs and
+    // the pair of padding rows below the tile, which is also the padding row above the next image), and
+    // virtual row 2 P i + y stands for row y of image i in both rings.  In step sigma group A is at position
+    // sigma of the stream, group B at sigma - 2, the epilogue of B's rows at sigma - 3, the loads at
+    // sigma + 2: nothing drains between images.
+    struct Pos {
+        int i, s; // image within the workgroup, step within the image
+    };
+    const int P = S + 1;
+    const int n_cnt = n_end - n_begin;
+    auto pos_of = [P](int sigma) {
+        const int i = sigma >= 0 ? sigma / P : -((P - 1 - sigma) / P);
+        return Pos{i, sigma - i * P};
+    };
+    auto advance = [P](Pos &p) {
+        if (++p.s == P) {
+            p.s = 0;
+            ++p.i;
         }
-        if (grp == 1)
-            for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
-        __builtin_amdgcn_s_waitcnt(kWaitVm0);
-        __syncthreads();
+    };
+    Pos pa = pos_of(0), pb = pos_of(-2), pf = pos_of(-3), pl = pos_of(2), p1 = pos_of(1);
+    auto tile_origin = [&](int n) {
+        int oy = 0, ox = 0;
+        if (src.off) {
+            oy = clampi(src.off[2 * n], 0, src.H - g.h);
+            ox = clampi(src.off[2 * n + 1], 0, src.W - g.w);
+        }
+        return src.img + (int64_t)n * 3 * plane + (int64_t)oy * src.W + ox;
+    };
 
-        // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 held in `a`
-        auto finish = [&](const f32x16 (&a)[RW], int j) {
-            const int ln = pin_in_loop(tid & 63);
-            const int pxl = ln & 31, hf = ln >> 5;
-            const int x = xb * 32 + pxl;
-            const float *si = &s_biasB[cb * 32 + hf * 16];
-            if (!LASTB) {
-                const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
-                const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
-#pragma unroll
-                for (int hq = 0; hq < 2; ++hq) {
-                    const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
-#pragma unroll
-                    for (int r = 0; r < RW; ++r) {
-                        u32x4 pk;
-                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
-                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
-                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
-                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
-                        bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
-                        if (full) *(u32x4 *)dst = pk;
-                        else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
-                    }
-                }
-            }
-            if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
-                strip_statistics<RW, LASTB>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
-                if (cb == 0 && ln == 0) {
-                    const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
-                    s_cnt[w4] += (float)(rows * cols);
-                }
-            }
-        };
+    // ---- before the first step: correction of the first image, its input rows -1 .. 4 (FIRST: -1 .. 2),
+    //      intermediate row -1 = zero
+    const uint8_t *tile0 = nullptr;
+    if (FIRST) {
+        tile0 = tile_origin(n_begin);
+        if (grp == 0) {
 #pragma unroll 1
-        for (int s = 0; s <= S + 2; ++s) {
-            if (grp == 0) {
-                const int ln = pin_in_loop(tid & 63);
-                const int pxl = ln & 31, hf = ln >> 5;
-                const int x = xb * 32 + pxl;
-                // FIRST: the raw pixels of rows 2s+3, 2s+4 (window of step s+1) start their way into registers
-                uint8_t pv[2] = {0, 0};
-                bool pin[2] = {false, false};
-                if (FIRST && 2 * s + 3 <= 2 * S) {
+            for (int y0 = -1; y0 <= 1; y0 += 2)
 #pragma unroll
-                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, 2 * s + 3, tid + 256 * k, pin[k]);
+                for (int k = 0; k < 2; ++k) {
+                    bool inside;
+                    const uint8_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside);
+                    pixel_store(y0, tid + 256 * k, v, inside);
                 }
-                if (s < S) {
-                    if (FIRST) {
-                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int r = 0; r < RW; ++r) {
-                            const int y = 2 * s + r;
-                            const uint8_t *lp[3];
-#pragma unroll
-                            for (int dy = 0; dy < 3; ++dy) lp[dy] = (const uint8_t *)&s_pix[slot_of(y - 1 + dy)][xb * 32 + pxl][0];
-                            bf16x8 bfrag[3];
-#pragma unroll
-                            for (int k = 0; k < 3; ++k) { // k chunk: taps 4k + 2 hf and 4k + 2 hf + 1 (beyond 8: zero weights, tap 8 re-read)
-                                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                                u32x2 two[2];
-#pragma unroll
-                                for (int j2 = 0; j2 < 2; ++j2) {
-                                    int tap = 4 * k + 2 * hf + j2;
-                                    tap = tap > 8 ? 8 : tap;
-                                    const int dy = tap / 3, dx = tap - dy * 3;
-                                    const uint8_t *p0 = dy == 0 ? lp[0] : (dy == 1 ? lp[1] : lp[2]);
-                                    two[j2] = *(const u32x2 *)(p0 + dx * 8);
-                                }
-                                const u32x4 both = {two[0][0], two[0][1], two[1][0], two[1][1]};
-                                bfrag[k] = __builtin_bit_cast(bf16x8, both);
-                            }
-                            acc[r] = mfma32(Wr[0][0], bfrag[0], zero);
-                            acc[r] = mfma32(Wr[0][1], bfrag[1], acc[r]);
-                            acc[r] = mfma32(Wr[0][2], bfrag[2], acc[r]);
-#pragma unroll
-                            for (int k = 0; k < 3; ++k) acc[r] = mfma32(Wr[1][k], bfrag[k], acc[r]);
-                        }
-                    } else {
-                        lrow_t rowp[RW + 2];
-#pragma unroll
-                        for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * s - 1 + r) * ROWB;
-                        strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
-                    }
-                    // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
-                    const float *si = &s_initA[cb * 32 + hf * 16];
-#pragma unroll
-                    for (int hq = 0; hq < 2; ++hq) {
-                        const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
-#pragma unroll
-                        for (int r = 0; r < RW; ++r) {
-                            const int y = 2 * s + r;
-                            u32x4 pk;
-                            pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
-                            pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
-                            pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
-                            pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
-                            if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
-                            *(u32x4 *)(ring_mid + slot_of(y) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
-                        }
-                    }
-                } else if (s == S) { // the rows below the tile: zero padding of the second block
-#pragma unroll
-                    for (int r = 0; r < RW; ++r)
-#pragma unroll
-                        for (int hq = 0; hq < 2; ++hq)
-                            *(u32x4 *)(ring_mid + slot_of(2 * s + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
-                                (u32x4){0u, 0u, 0u, 0u};
-                }
-                if (FIRST && s >= 3 && s - 3 < S) { // the rows group B accumulated in the previous step
-                    const int j = s - 3;
-                    const float *srcx = &s_accx[(((j & 1) * 4 + w4) * 8) * 256 + ln * 4];
-                    f32x16 a[RW];
-#pragma unroll
-                    for (int r = 0; r < RW; ++r)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const f32x4 v = *(const f32x4 *)(srcx + (r * 4 + q) * 256);
-                            a[r][4 * q] = v[0]; a[r][4 * q + 1] = v[1]; a[r][4 * q + 2] = v[2]; a[r][4 * q + 3] = v[3];
-                        }
-                    finish(a, j);
-                }
-                if (FIRST && 2 * s + 3 <= 2 * S) { // their slots were last read two steps ago
-#pragma unroll
-                    for (int k = 0; k < 2; ++k) pixel_store(2 * s + 3, tid + 256 * k, pv[k], pin[k]);
-                }
-            } else {
-                const int ln = pin_in_loop(tid & 63);
-                const int pxl = ln & 31, hf = ln >> 5;
-                const int x = xb * 32 + pxl;
-                if (!FIRST && s >= 3 && s - 3 < S) finish(acc, s - 3); // the rows accumulated in the previous step
-                if (s >= 2 && s - 2 < S) {
-                    const int j = s - 2;
-                    lrow_t rowp[RW + 2];
-#pragma unroll
-                    for (int r = 0; r < RW + 2; ++r) rowp[r] = mid_base + (uint32_t)slot_of(2 * j - 1 + r) * ROWB;
-                    strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
-                    if (FIRST) { // group A finishes these rows in the next step
-                        float *dst = &s_accx[(((j & 1) * 4 + w4) * 8) * 256 + ln * 4];
-#pragma unroll
-                        for (int r = 0; r < RW; ++r)
-#pragma unroll
-                            for (int q = 0; q < 4; ++q)
-                                *(f32x4 *)(dst + (r * 4 + q) * 256) = (f32x4){acc[r][4 * q], acc[r][4 * q + 1], acc[r][4 * q + 2], acc[r][4 * q + 3]};
-                    }
-                }
-            }
-            // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
-            // date from the start of this step) is done, then the rows needed two steps from now are put on
-            // their way, one row per group.
-            if (!FIRST) {
-                __builtin_amdgcn_s_waitcnt(kWaitVm0);
-                if (2 * s + 5 + grp <= 2 * S) issue_row(n, 2 * s + 5 + grp);
-            }
-            lds_barrier();
         }
-        // ---- this image's channel sums -> its records; accumulators cleared
-        if (grp == kFinishGroup && st.tout) {
-            const int ln = pin_in_loop(tid & 63);
+    } else {
+#pragma unroll 1
+        for (int v = -1 + grp; v <= 4; v += 2) { // first, so that they travel while the correction is computed
+            const int i = (v + 1) / (2 * P);     // a tile of one or two rows: rows 3, 4 of the stream are the next image's
+            if (i < n_cnt) issue_row(n_begin + i, v - 2 * P * i, v);
+        }
+        if (grp == 0) prepare_init(n_begin);
+    }
+    if (grp == 1)
+        for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();
+
+    // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 of image n held in `a`;
+    // after the last row pair of an image its channel sums go to its records and the accumulators are cleared
+    auto finish = [&](const f32x16 (&a)[RW], int n, int j) {
+        const int ln = pin_in_loop(tid & 63);
+        const int pxl = ln & 31, hf = ln >> 5;
+        const int x = xb * 32 + pxl;
+        const float *si = &s_biasB[cb * 32 + hf * 16];
+        if (!LASTB) {
+            const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+            const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
+#pragma unroll
+            for (int hq = 0; hq < 2; ++hq) {
+                const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                for (int r = 0; r < RW; ++r) {
+                    u32x4 pk;
+                    pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
+                    pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
+                    pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
+                    pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                    bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                    if (full) *(u32x4 *)dst = pk;
+                    else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                }
+            }
+        }
+        if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
+            strip_statistics<RW, LASTB>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
+            if (cb == 0 && ln == 0) {
+                const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
+                s_cnt[w4] += (float)(rows * cols);
+            }
+        }
+        if (st.tout && j == S - 1) { // what this wavefront gathered for the image (its own part of s_stat)
             float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, NQ);
             if (ln < 32) {
 #pragma unroll
@@ -1018,6 +922,149 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 s_cnt[w4] = 0.f;
             }
         }
+    };
+
+    f32x16 acc[RW];
+    const int n_steps = n_cnt * P + 2;
+#pragma unroll 1
+    for (int sg = 0; sg < n_steps; ++sg) {
+        const bool fin = pf.i >= 0 && pf.i < n_cnt && pf.s < S; // rows accumulated in the previous step wait for their epilogue
+        if (grp == 0) {
+            const int ln = pin_in_loop(tid & 63);
+            const int pxl = ln & 31, hf = ln >> 5;
+            const int x = xb * 32 + pxl;
+            // FIRST: the raw pixels of virtual rows 2sg+3, 2sg+4 (window of step sg+1) start their way into registers
+            uint8_t pv[2] = {0, 0};
+            bool pin[2] = {false, false};
+            bool fetch = false;
+            if (FIRST && p1.i < n_cnt) {
+                int y0 = 2 * p1.s + 1;
+                fetch = true;
+                if (p1.s == S) { // rows -1, 0 of the next image
+                    fetch = p1.i + 1 < n_cnt;
+                    y0 = -1;
+                    if (fetch) tile0 = tile_origin(n_begin + p1.i + 1);
+                }
+                if (fetch) {
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, y0, tid + 256 * k, pin[k]);
+                }
+            }
+            if (pa.i < n_cnt && pa.s < S) {
+                if (FIRST) {
+                    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        const int vy = 2 * sg + r;
+                        const uint8_t *lp[3];
+#pragma unroll
+                        for (int dy = 0; dy < 3; ++dy) lp[dy] = (const uint8_t *)&s_pix[slot_of(vy - 1 + dy)][xb * 32 + pxl][0];
+                        bf16x8 bfrag[3];
+#pragma unroll
+                        for (int k = 0; k < 3; ++k) { // k chunk: taps 4k + 2 hf and 4k + 2 hf + 1 (beyond 8: zero weights, tap 8 re-read)
+                            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                            u32x2 two[2];
+#pragma unroll
+                            for (int j2 = 0; j2 < 2; ++j2) {
+                                int tap = 4 * k + 2 * hf + j2;
+                                tap = tap > 8 ? 8 : tap;
+                                const int dy = tap / 3, dx = tap - dy * 3;
+                                const uint8_t *p0 = dy == 0 ? lp[0] : (dy == 1 ? lp[1] : lp[2]);
+                                two[j2] = *(const u32x2 *)(p0 + dx * 8);
+                            }
+                            const u32x4 both = {two[0][0], two[0][1], two[1][0], two[1][1]};
+                            bfrag[k] = __builtin_bit_cast(bf16x8, both);
+                        }
+                        acc[r] = mfma32(Wr[0][0], bfrag[0], zero);
+                        acc[r] = mfma32(Wr[0][1], bfrag[1], acc[r]);
+                        acc[r] = mfma32(Wr[0][2], bfrag[2], acc[r]);
+#pragma unroll
+                        for (int k = 0; k < 3; ++k) acc[r] = mfma32(Wr[1][k], bfrag[k], acc[r]);
+                    }
+                } else {
+                    lrow_t rowp[RW + 2];
+#pragma unroll
+                    for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * sg - 1 + r) * ROWB;
+                    strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                }
+                // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
+                const float *si = &s_initA[cb * 32 + hf * 16];
+#pragma unroll
+                for (int hq = 0; hq < 2; ++hq) {
+                    const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        const int y = 2 * pa.s + r;
+                        u32x4 pk;
+                        pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
+                        pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
+                        pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
+                        pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                        if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
+                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
+                    }
+                }
+            } else if (pa.i < n_cnt) { // the rows below the tile: zero padding of the second block (and above the next image)
+#pragma unroll
+                for (int r = 0; r < RW; ++r)
+#pragma unroll
+                    for (int hq = 0; hq < 2; ++hq)
+                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
+                            (u32x4){0u, 0u, 0u, 0u};
+                if (!FIRST && pa.i + 1 < n_cnt) prepare_init(n_begin + pa.i + 1); // nobody reads s_initA in this step
+            }
+            if (FIRST && fin) { // the rows group B accumulated in the previous step
+                const float *srcx = &s_accx[((((sg - 3) & 1) * 4 + w4) * 8) * 256 + ln * 4];
+                f32x16 a[RW];
+#pragma unroll
+                for (int r = 0; r < RW; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4 v = *(const f32x4 *)(srcx + (r * 4 + q) * 256);
+                        a[r][4 * q] = v[0]; a[r][4 * q + 1] = v[1]; a[r][4 * q + 2] = v[2]; a[r][4 * q + 3] = v[3];
+                    }
+                finish(a, n_begin + pf.i, pf.s);
+            }
+            if (FIRST && fetch) { // their slots were last read two steps ago
+#pragma unroll
+                for (int k = 0; k < 2; ++k) pixel_store(2 * sg + 3, tid + 256 * k, pv[k], pin[k]);
+            }
+        } else {
+            const int ln = pin_in_loop(tid & 63);
+            if (!FIRST && fin) finish(acc, n_begin + pf.i, pf.s); // the rows accumulated in the previous step
+            if (pb.i >= 0 && pb.i < n_cnt && pb.s < S) {
+                lrow_t rowp[RW + 2];
+#pragma unroll
+                for (int r = 0; r < RW + 2; ++r) rowp[r] = mid_base + (uint32_t)slot_of(2 * (sg - 2) - 1 + r) * ROWB;
+                strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                if (FIRST) { // group A finishes these rows in the next step
+                    float *dst = &s_accx[((((sg - 2) & 1) * 4 + w4) * 8) * 256 + ln * 4];
+#pragma unroll
+                    for (int r = 0; r < RW; ++r)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            *(f32x4 *)(dst + (r * 4 + q) * 256) = (f32x4){acc[r][4 * q], acc[r][4 * q + 1], acc[r][4 * q + 2], acc[r][4 * q + 3]};
+                }
+            }
+        }
+        // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
+        // date from the start of this step) is done, then the rows needed two steps from now are put on
+        // their way, one row per group: rows 2s+1, 2s+2 of the image of step sg + 2, or rows -1, 0 of the
+        // image after it when that step is the one of the padding rows.
+        if (!FIRST) {
+            __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            if (pl.i < n_cnt) {
+                const bool nxt = pl.s == S;
+                const int li = pl.i + (nxt ? 1 : 0);
+                if (li < n_cnt) issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1) + grp, 2 * sg + 5 + grp);
+            }
+        }
+        lds_barrier();
+        advance(pa);
+        advance(pb);
+        advance(pf);
+        advance(pl);
+        advance(p1);
     }
 }
 

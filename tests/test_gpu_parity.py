@@ -201,6 +201,45 @@ def test_extractor_forward_logits_and_bits(qrm, name, C, nb, nbits, h, w, N):
     ctx.close()
 
 
+STREAM_CASES = [   # name, blocks, bits, h, w, images: several images per workgroup (one launch for all of them)
+    ("8x16 b4, 1100 images", 4, 24, 8, 16, 1100),
+    ("23x50 b5, 520 images", 5, 48, 23, 50, 520),
+    ("5x64 b3, 1500 images", 3, 16, 5, 64, 1500),
+    ("2x9 b2, 777 images", 2, 8, 2, 9, 777),
+    ("1x64 b4, 600 images", 4, 16, 1, 64, 600),
+    ("7x33 b6, 513 images", 6, 32, 7, 33, 513),
+]
+
+
+@pytest.mark.parametrize("name,nb,nbits,h,w,N", STREAM_CASES, ids=[c[0] for c in STREAM_CASES])
+def test_extractor_stream_of_images_per_workgroup(qrm, name, nb, nbits, h, w, N):
+    """More images than compute units in one micro-batch: a workgroup of the fused kernels walks through several
+    images without draining its pipeline in between (rows of consecutive images share the LDS rings)."""
+    wts = small_weights(64, nb, nbits, nb * 5 + nbits)
+    rng = np.random.default_rng(nbits * 3 + h)
+    tiles = rng.integers(0, 256, size=(N, 3, h, w), dtype=np.uint8)
+    tiles[N // 2] = 0                              # a black and a white image in the middle of the stream
+    tiles[N // 2 + 1] = 255
+    ref_logits, _ = oracle.extractor_forward(wts, tiles)
+    ctx = qrm.Context(weights=wts)
+    for mb in (0, 300):                            # default (all images at once) and a ragged split
+        ctx.qrm_set_micro_batch(mb)
+        d_logits, d_bits = empty((N, nbits), torch.float32), empty((N, nbits), torch.uint8)
+        ctx.qrm_extractor_forward(dev(tiles), N, h, w, d_logits, d_bits)
+        torch.cuda.synchronize()
+        g, gb = d_logits.cpu().numpy(), d_bits.cpu().numpy()
+        rest = np.ones(N, dtype=bool)
+        rest[N // 2:N // 2 + 2] = False
+        check_logits(g[rest], ref_logits[rest], gb[rest], what=f"{name}, micro-batch {mb}")
+        # A constant image is the worst case of bf16 activations: every pixel of a channel carries the same
+        # value, so its rounding error (up to 2^-9 relative per block) is the same everywhere and survives the
+        # average pool instead of averaging out.  Measured up to 3.4e-2 (fused or not); bound kept apart.
+        flat = np.abs(g[~rest] - ref_logits[~rest]) / np.maximum(1.0, np.abs(ref_logits[~rest]))
+        print(f"[parity] {name}, micro-batch {mb}: constant images, max scaled logit error {flat.max():.3e} (limit 8e-2)")
+        assert flat.max() <= 8e-2
+    ctx.close()
+
+
 def test_extractor_final_relu_and_affine(qrm):
     wts = small_weights(64, 2, 48, 99)
     g = np.random.default_rng(9)
