@@ -161,7 +161,15 @@ def main() -> int:
     t_vk = timed(lambda: ctx.qrm_verify_key(vmsg, n_vw, vmat, vdet, stream=stream))
     vk_bytes = n_vw * (cfg.k + 5)
     del vmsg, vmat, vdet
+    # variance-based tile selection: reads every pixel once (all of the image lies under some window)
+    sel_off = torch.empty((N, 2), dtype=torch.int32, device="cuda")
+    t_sel = timed(lambda: ctx.qrm_select_tiles_variance(d_img, N, cfg.H, cfg.W, cfg.tile, cfg.tile // 2, sel_off,
+                                                        None, stream=stream))
+    sel_bytes = N * (3 * cfg.H * cfg.W + 8)
     stages = {
+        "select_tiles_variance": {"us": round(t_sel * 1e6, 2), "images_per_s": round(N / t_sel, 0),
+                                  "algorithmic_GBs": round(sel_bytes / t_sel / 1e9, 1),
+                                  "frac_hbm": round(sel_bytes / t_sel / 1e9 / PEAK_HBM_GBS, 4), "images": N},
         "verify_key": {"us": round(t_vk * 1e6, 2), "words_per_s": round(n_vw / t_vk, 0),
                        "algorithmic_GBs": round(vk_bytes / t_vk / 1e9, 1),
                        "frac_hbm": round(vk_bytes / t_vk / 1e9 / PEAK_HBM_GBS, 4), "words": n_vw},

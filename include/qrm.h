@@ -131,6 +131,25 @@ QRM_API qrm_status qrm_extract_tiles(qrm_ctx *ctx, const uint8_t *d_images, int6
                              const int32_t *d_off_yx, int32_t tile, uint8_t *d_tiles, void *stream);
 
 /*
+ * Variance-based tile selection (Listing 1, the user-defined strategy `select_patch`): windows of
+ * tile x tile pixels at `stride` (the listing: 64 and 32), the variance of every window per channel,
+ * summed over the channels; the window with the largest sum is the image's tile.  Readings: argmax over
+ * all windows, the first in row-major order on ties; unbiased variance; the image as the extractor sees
+ * it, i.e. channel c divided by std_c, so that its variance counts with weight w_c = inv_std_c^2
+ * (inv_std_c = (float)(1.0 / std_c) as stored at qrm_create; w = 1 when the context has no extractor).
+ * Exact form: with n = tile^2, S1 = sum x, S2 = sum x^2 over the window's raw bytes of channel c,
+ * V_c = n S2 - S1^2 (an integer = n (n-1) variance), score = ((V_0 w_0) + V_1 w_1) + V_2 w_2 in IEEE
+ * float64, each product and sum rounded once.
+ * d_images u8 [N,3,H,W]; d_off_yx i32 [N,2] (y, x) receives the origins, ready for qrm_detect;
+ * d_scores f64 [N, nH*nW] or NULL, nH = (H-tile)/stride + 1, nW likewise, windows in row-major order.
+ * Errors: QRM_E_INVALID (tile or stride <= 0, tile > H or W, NULL pointer), QRM_E_UNSUPPORTED (tile not
+ * a multiple of stride, tile > 512, stride > 256, more than 1024 stride x stride cells under the windows).
+ */
+QRM_API qrm_status qrm_select_tiles_variance(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, int32_t H,
+                                             int32_t W, int32_t tile, int32_t stride, int32_t *d_off_yx,
+                                             double *d_scores, void *stream);
+
+/*
  * Extractor forward pass on raw tiles (Section 4.1, m' = H_D(tile); hard bit = (logit > 0)).
  * d_tiles u8 [N,3,h,w] raw bytes, normalised inside the first convolution.
  * d_logits f32 [N,n_bits]; d_bits u8 [N,n_bits] with values 0/1, may be NULL.

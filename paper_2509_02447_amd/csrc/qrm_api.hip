@@ -704,6 +704,28 @@ qrm_status qrm_extract_tiles(qrm_ctx *c, const uint8_t *d_images, int64_t N, int
     return QRM_OK;
 }
 
+qrm_status qrm_select_tiles_variance(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                                     int32_t tile, int32_t stride, int32_t *d_off_yx, double *d_scores, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (tile <= 0 || stride <= 0 || H <= 0 || W <= 0 || tile > H || tile > W)
+        return fail(c, QRM_E_INVALID, "need 0 < tile <= H, W and stride > 0");
+    if (!select_tiles_supported(H, W, tile, stride))
+        return fail(c, QRM_E_UNSUPPORTED, "tile must be a multiple of stride, tile <= 512, stride <= 256, at most 1024 cells");
+    if (N == 0) return QRM_OK;
+    if (!d_images || !d_off_yx) return fail(c, QRM_E_INVALID, "d_images / d_off_yx is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    // the extractor sees channel c scaled by 1/std_c: its variance counts with the square of that
+    double w[3] = {1.0, 1.0, 1.0};
+    if (c->has_ext)
+        for (int i = 0; i < 3; ++i) w[i] = (double)c->inv_std[i] * (double)c->inv_std[i];
+    e = launch_select_tiles_variance(d_images, N, H, W, tile, stride, w, d_off_yx, d_scores, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(c, e, "select_tiles launch");
+    return QRM_OK;
+}
+
 static qrm_status extractor_common(qrm_ctx *c, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w, int n_run,
                                    float *d_logits, uint8_t *d_bits, float *d_act, void *stream)
 {

@@ -122,6 +122,12 @@ hipError_t launch_rs_decode(const RsParams &p, const uint8_t *sym, int64_t N, ui
 // matches / detected for messages already in memory (msg device [N,k])
 hipError_t launch_verify(const RsParams &p, const uint8_t *msg, int64_t N, const KeyArgs &key, hipStream_t s);
 
+// Variance-based tile selection: origin of the first window with the largest weighted sum of channel variances.
+// off_yx device [N,2]; scores device [N, nH*nW] or null; w: channel weights.
+bool select_tiles_supported(int H, int W, int win, int stride);
+hipError_t launch_select_tiles_variance(const uint8_t *img, int64_t N, int H, int W, int win, int stride,
+                                        const double w[3], int32_t *off_yx, double *scores, hipStream_t s);
+
 // host-side helpers
 uint16_t f32_to_bf16_rne(float f);
 

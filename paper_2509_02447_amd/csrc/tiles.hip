@@ -2,6 +2,7 @@
 // window at a per-image origin out of each of the three u8 planes.  HBM-bound byte shuffling: one
 // block per (image, plane); when everything is 4-byte friendly each lane assembles one aligned output
 // dword from two aligned input dwords (funnel shift by the source misalignment), otherwise bytes.
+// Also here: variance-based tile selection (further down).
 #include "qrm_internal.h"
 
 namespace qrm {
@@ -50,7 +51,175 @@ __global__ __launch_bounds__(256) void extract_tiles_kernel(const uint8_t *__res
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Variance-based tile selection (Listing 1 of the paper, `select_patch`): windows of win x win pixels at
+// a stride that divides win; score of a window = sum over channels of w_c * (n S2_c - S1_c^2), i.e. the
+// channel's unbiased variance up to the common factor n (n-1); the first window with the largest score
+// is the tile.  HBM-bound: every pixel that lies in some window is read exactly once.
+//
+// One workgroup per image.  The image is cut into cells of stride x stride pixels; a window is a square of
+// (win / stride)^2 cells.  Phase 1: every lane walks down a run of rows of one 16-byte (or 1-byte) column
+// chunk, sums x (v_sad_u8) and x^2 (v_dot4_u32_u8) in registers and adds them to the cell's 32-bit sums in
+// LDS when it crosses into the next cell row.  Phase 2: one lane per window adds up its cells (64 bit),
+// forms the exact integers n S2 - S1^2, and the score in float64 in a fixed order with no fused
+// multiply-add; a workgroup reduction picks the first maximum.
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxCells = 1024; // cells per channel a workgroup can hold
+
+struct SelectArgs {
+    int H, W, win, stride;
+    int nH, nW;     // windows
+    int nCy, nCx;   // cells that lie in some window
+    double w[3];    // channel weights
+};
+
+template <int VEC>
+__global__ __launch_bounds__(256) void tile_variance_kernel(const uint8_t *__restrict__ img, SelectArgs a,
+                                                            int32_t *__restrict__ off_yx, double *__restrict__ scores)
+{
+    __shared__ uint32_t s_sum[3][kMaxCells], s_sq[3][kMaxCells];
+    __shared__ double s_best[256];
+    __shared__ int s_idx[256];
+    const int tid = threadIdx.x;
+    const int64_t n = blockIdx.x;
+    const int cells = a.nCy * a.nCx;
+    for (int i = tid; i < 3 * kMaxCells; i += 256) {
+        (&s_sum[0][0])[i] = 0u;
+        (&s_sq[0][0])[i] = 0u;
+    }
+    __syncthreads();
+
+    // ---- phase 1: cell sums
+    const int Hc = a.nCy * a.stride, Wc = a.nCx * a.stride; // the part of the image that windows cover
+    const int ncx = Wc / VEC;                                // column chunks per row
+    const int TX = ncx < 256 ? ncx : 256;
+    const int n_rg = 256 / TX;                               // row groups
+    const int R = (Hc + n_rg - 1) / n_rg;                    // rows per group
+    const int rg = tid / TX;
+    const uint8_t *base = img + n * 3 * (int64_t)a.H * a.W;
+    if (rg < n_rg) {
+        const int r0 = rg * R, r1 = min(Hc, r0 + R);
+        for (int c = 0; c < 3; ++c) {
+            const uint8_t *plane = base + (int64_t)c * a.H * a.W;
+            for (int cx = tid - rg * TX; cx < ncx; cx += TX) {
+                const int cellx = cx * VEC / a.stride;
+                const uint8_t *col = plane + cx * VEC;
+                for (int seg = r0; seg < r1;) { // the run's rows, one cell row at a time
+                    const int cy = seg / a.stride;
+                    const int seg_end = min(r1, (cy + 1) * a.stride);
+                    uint32_t s1 = 0, s2 = 0;
+#pragma unroll 4
+                    for (int r = seg; r < seg_end; ++r) { // independent loads: several in flight per lane
+                        const uint8_t *p = col + (int64_t)r * a.W;
+                        if (VEC == 16) {
+                            const uint4 v = *(const uint4 *)p;
+                            s1 = __builtin_amdgcn_sad_u8(v.x, 0u, s1);
+                            s1 = __builtin_amdgcn_sad_u8(v.y, 0u, s1);
+                            s1 = __builtin_amdgcn_sad_u8(v.z, 0u, s1);
+                            s1 = __builtin_amdgcn_sad_u8(v.w, 0u, s1);
+                            s2 = __builtin_amdgcn_udot4(v.x, v.x, s2, false);
+                            s2 = __builtin_amdgcn_udot4(v.y, v.y, s2, false);
+                            s2 = __builtin_amdgcn_udot4(v.z, v.z, s2, false);
+                            s2 = __builtin_amdgcn_udot4(v.w, v.w, s2, false);
+                        } else {
+                            const uint32_t x = *p;
+                            s1 += x;
+                            s2 += x * x;
+                        }
+                    }
+                    atomicAdd(&s_sum[c][cy * a.nCx + cellx], s1);
+                    atomicAdd(&s_sq[c][cy * a.nCx + cellx], s2);
+                    seg = seg_end;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    (void)cells;
+
+    // ---- phase 2: window scores, first maximum
+    const int k = a.win / a.stride;
+    const double npix = (double)a.win * (double)a.win; // exact
+    double best = -1.0;                               // scores are >= 0
+    int best_idx = 0x7fffffff;
+    for (int wi = tid; wi < a.nH * a.nW; wi += 256) {
+        const int wy = wi / a.nW, wx = wi - wy * a.nW;
+        double score = 0.0;
+        for (int c = 0; c < 3; ++c) {
+#pragma clang fp contract(off) // each product and each sum is rounded on its own: no fused multiply-add
+            unsigned long long S1 = 0, S2 = 0;
+            for (int dy = 0; dy < k; ++dy)
+                for (int dx = 0; dx < k; ++dx) {
+                    S1 += s_sum[c][(wy + dy) * a.nCx + wx + dx];
+                    S2 += s_sq[c][(wy + dy) * a.nCx + wx + dx];
+                }
+            const unsigned long long v = (unsigned long long)(a.win * a.win) * S2 - S1 * S1; // exact, < 2^53
+            const double term = (double)v * a.w[c];
+            score = c == 0 ? term : score + term;
+        }
+        (void)npix;
+        if (scores) scores[n * (int64_t)(a.nH * a.nW) + wi] = score;
+        if (score > best) { // ascending wi: the first maximum stays
+            best = score;
+            best_idx = wi;
+        }
+    }
+    s_best[tid] = best;
+    s_idx[tid] = best_idx;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if (tid < half) {
+            const double o = s_best[tid + half];
+            const int oi = s_idx[tid + half];
+            if (o > s_best[tid] || (o == s_best[tid] && oi < s_idx[tid])) {
+                s_best[tid] = o;
+                s_idx[tid] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const int wi = s_idx[0];
+        off_yx[2 * n] = wi / a.nW * a.stride;
+        off_yx[2 * n + 1] = wi % a.nW * a.stride;
+    }
+}
+
 } // namespace
+
+bool select_tiles_supported(int H, int W, int win, int stride)
+{
+    if (win <= 0 || stride <= 0 || win > H || win > W || win % stride != 0 || win > 512 || stride > 256) return false;
+    const int nH = (H - win) / stride + 1, nW = (W - win) / stride + 1, k = win / stride;
+    return (int64_t)(nH - 1 + k) * (nW - 1 + k) <= kMaxCells;
+}
+
+hipError_t launch_select_tiles_variance(const uint8_t *img, int64_t N, int H, int W, int win, int stride,
+                                        const double w[3], int32_t *off_yx, double *scores, hipStream_t s)
+{
+    if (N <= 0) return hipSuccess;
+    SelectArgs a{};
+    a.H = H; a.W = W; a.win = win; a.stride = stride;
+    a.nH = (H - win) / stride + 1;
+    a.nW = (W - win) / stride + 1;
+    const int k = win / stride;
+    a.nCy = a.nH - 1 + k;
+    a.nCx = a.nW - 1 + k;
+    for (int c = 0; c < 3; ++c) a.w[c] = w[c];
+    // 16-byte loads: chunks must not straddle cells and every row of every image must start 16-byte aligned
+    const bool wide = stride % 16 == 0 && W % 16 == 0 && ((uintptr_t)img & 15u) == 0;
+    const int64_t kMaxGrid = 1LL << 30;
+    for (int64_t n0 = 0; n0 < N; n0 += kMaxGrid) {
+        const int64_t cnt = N - n0 < kMaxGrid ? N - n0 : kMaxGrid;
+        const uint8_t *img0 = img + n0 * 3 * (int64_t)H * W;
+        double *sc0 = scores ? scores + n0 * (int64_t)(a.nH * a.nW) : nullptr;
+        if (wide)
+            hipLaunchKernelGGL(tile_variance_kernel<16>, dim3((unsigned)cnt), dim3(256), 0, s, img0, a, off_yx + 2 * n0, sc0);
+        else
+            hipLaunchKernelGGL(tile_variance_kernel<1>, dim3((unsigned)cnt), dim3(256), 0, s, img0, a, off_yx + 2 * n0, sc0);
+    }
+    return hipGetLastError();
+}
 
 hipError_t launch_extract_tiles(const uint8_t *img, int64_t N, int H, int W, const int32_t *off, int tile,
                                 uint8_t *out, hipStream_t s)

@@ -423,6 +423,108 @@ def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
 
 # ---------------------------------------------------------------- error paths (host side only)
 
+# ---------------------------------------------------------------- variance-based tile selection
+
+from oracle import tileselect
+
+
+def channel_weights(std):
+    """What the library holds: inv_std = (float)(1.0 / std) at context creation, weight = its square in float64."""
+    inv = (1.0 / np.asarray(std, dtype=np.float32).astype(np.float64)).astype(np.float32).astype(np.float64)
+    return inv * inv
+
+
+SELECT_CASES = [  # N, H, W, tile, stride
+    (33, 256, 256, 64, 32),      # the listing's sizes on the benchmark's images (wide loads)
+    (5, 96, 144, 32, 16),
+    (4, 512, 512, 128, 64),      # configuration C4
+    (7, 100, 117, 30, 15),       # nothing aligned: byte loads, rows and columns left over
+    (3, 64, 128, 64, 64),        # stride = tile: two windows side by side
+    (6, 40, 40, 40, 40),         # a single window
+    (2, 256, 256, 32, 8),        # 29 x 29 windows, 32 x 32 cells
+]
+
+
+@pytest.mark.parametrize("N,H,W,tile,stride", SELECT_CASES)
+def test_select_tiles_variance_bit_exact(qrm, N, H, W, tile, stride):
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    rng = np.random.default_rng(H * 7 + W + tile)
+    imgs = rng.integers(0, 256, size=(N, 3, H, W), dtype=np.uint8)
+    # structure, so that windows differ by more than noise: a flat image, a flat image with one busy window,
+    # two equally busy windows (tie), a gradient
+    imgs[0] = 131
+    if N > 1:
+        imgs[1] = 90
+        y0, x0 = (H - tile) // stride * stride, min(stride, (W - tile) // stride * stride)
+        imgs[1, :, y0:y0 + tile, x0:x0 + tile] = rng.integers(0, 256, size=(3, tile, tile), dtype=np.uint8)
+    if N > 2 and W >= 2 * tile and (W - tile) % stride == 0:
+        imgs[2] = 17
+        patch = rng.integers(0, 256, size=(3, tile, tile), dtype=np.uint8)
+        imgs[2, :, 0:tile, 0:tile] = patch
+        imgs[2, :, H - tile:H, W - tile:W] = patch if (H - tile) % stride == 0 else 17
+    ref_off, ref_scores = tileselect.select_tiles_variance(imgs, tile, stride, channel_weights(wts["std"]))
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    nwin = ref_scores.shape[1]
+    d_off, d_sc = empty((N, 2), torch.int32), empty((N, nwin), torch.float64)
+    ctx.qrm_select_tiles_variance(dev(imgs), N, H, W, tile, stride, d_off, d_sc)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_sc.cpu().numpy(), ref_scores), "window scores differ (float64, bit for bit)"
+    assert np.array_equal(d_off.cpu().numpy(), ref_off)
+    assert ref_off[0].tolist() == [0, 0]
+    d_off2 = empty((N, 2), torch.int32)
+    ctx.qrm_select_tiles_variance(dev(imgs), N, H, W, tile, stride, d_off2, None)     # scores are optional
+    torch.cuda.synchronize()
+    assert np.array_equal(d_off2.cpu().numpy(), ref_off)
+    ctx.close()
+    # a context without an extractor weighs the channels equally
+    rs_only = qrm.Context(rs=rs_dict(cfg))
+    rs_only.qrm_select_tiles_variance(dev(imgs), N, H, W, tile, stride, d_off, d_sc)
+    torch.cuda.synchronize()
+    ro, rsx = tileselect.select_tiles_variance(imgs, tile, stride, [1.0, 1.0, 1.0])
+    assert np.array_equal(d_sc.cpu().numpy(), rsx) and np.array_equal(d_off.cpu().numpy(), ro)
+    rs_only.close()
+
+
+def test_select_tiles_then_detect_equals_oracle_path(qrm):
+    """Selection feeds detection: the origins chosen on the device, then the whole path, against the oracle's."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = 24
+    imgs = synth.images(cfg, 0, N).copy()
+    rng = np.random.default_rng(3)
+    for i in range(N):                               # make one window per image clearly the busiest
+        imgs[i] = (imgs[i] // 4 + 96).astype(np.uint8)
+        wy, wx = rng.integers(0, 7, size=2)
+        imgs[i, :, wy * 32:wy * 32 + 64, wx * 32:wx * 32 + 64] = rng.integers(0, 256, size=(3, 64, 64), dtype=np.uint8)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    d_imgs, d_off = dev(imgs), empty((N, 2), torch.int32)
+    ctx.qrm_select_tiles_variance(d_imgs, N, cfg.H, cfg.W, cfg.tile, cfg.tile // 2, d_off)
+    d_logits, d_bits = empty((N, cfg.n_bits), torch.float32), empty((N, cfg.n_bits), torch.uint8)
+    d_msg, d_cw, d_ne = empty((N, cfg.k), torch.uint8), empty((N, cfg.n), torch.uint8), empty((N,), torch.int8)
+    ctx.qrm_detect(d_imgs, N, cfg.H, cfg.W, d_off, cfg.tile, d_logits, d_bits, d_msg, d_cw, d_ne)
+    torch.cuda.synchronize()
+    off, _ = tileselect.select_tiles_variance(imgs, cfg.tile, cfg.tile // 2, channel_weights(wts["std"]))
+    assert np.array_equal(d_off.cpu().numpy(), off)
+    got = dict(logits=d_logits.cpu().numpy(), bits=d_bits.cpu().numpy(), msg=d_msg.cpu().numpy(),
+               codeword=d_cw.cpu().numpy(), nerr=d_ne.cpu().numpy())
+    check_detect(cfg, wts, imgs, off, got, "C2 detect on variance-selected tiles")
+    ctx.close()
+
+
+def test_select_tiles_error_statuses(qrm):
+    cfg = synth.CONFIGS["C1"]
+    ctx = qrm.Context(rs=rs_dict(cfg))
+    d_img, d_off = empty((2, 3, 64, 64), torch.uint8), empty((2, 2), torch.int32)
+    for tile, stride in ((0, 8), (16, 0), (80, 8), (24, 16), (32, 1)):      # last: 33 x 33 cells
+        with pytest.raises(qrm.QrmError):
+            ctx.qrm_select_tiles_variance(d_img, 2, 64, 64, tile, stride, d_off)
+    with pytest.raises(qrm.QrmError):
+        ctx.qrm_select_tiles_variance(d_img, 2, 64, 64, 16, 8, None)
+    ctx.qrm_select_tiles_variance(d_img, 0, 64, 64, 16, 8, d_off)           # empty batch
+    ctx.close()
+
+
 # ---------------------------------------------------------------- key verification
 
 from oracle import keycheck
