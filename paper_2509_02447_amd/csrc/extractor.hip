@@ -883,21 +883,37 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         const int x = xb * 32 + pxl;
         const float *si = &s_biasB[cb * 32 + hf * 16];
         if (!LASTB) {
-            const uint32_t e0 = (uint32_t)(((n * g.h + 2 * j) * g.w + x) * C + cb * 32 + hf * 16);
+            // address = uniform start of the row pair + what the lane adds (the same in every step)
+            bf16_t *rows = out + (uint32_t)((n * g.h + 2 * j) * g.w * C);
+            const uint32_t le = (uint32_t)(x * C + cb * 32 + hf * 16);
             const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
+            if (full) { // the common case: straight-line code, no predicates
 #pragma unroll
-            for (int hq = 0; hq < 2; ++hq) {
-                const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+                for (int hq = 0; hq < 2; ++hq) {
+                    const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
-                for (int r = 0; r < RW; ++r) {
-                    u32x4 pk;
-                    pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
-                    pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
-                    pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
-                    pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
-                    bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
-                    if (full) *(u32x4 *)dst = pk;
-                    else if (2 * j + r < g.h && x < g.w) *(u32x4 *)dst = pk;
+                    for (int r = 0; r < RW; ++r) {
+                        u32x4 pk;
+                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
+                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
+                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
+                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                        *(u32x4 *)(rows + (le + (uint32_t)(r * kTileW * C + 8 * hq))) = pk;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int hq = 0; hq < 2; ++hq) {
+                    const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
+#pragma unroll
+                    for (int r = 0; r < RW; ++r) {
+                        u32x4 pk;
+                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
+                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
+                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
+                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                        if (2 * j + r < g.h && x < g.w) *(u32x4 *)(rows + (le + (uint32_t)(r * g.w * C + 8 * hq))) = pk;
+                    }
                 }
             }
         }
