@@ -290,12 +290,15 @@ __device__ __forceinline__ void lds_accumulate(float *slot16, const float (&tv)[
     }
 }
 
+// Four values of one lane into the wavefront's accumulators with LDS add instructions that return nothing:
+// no round trip to wait for (a read-modify-write costs one per call, a dozen per step in the last block).
+// Every accumulator has one writer (one lane of one wavefront), LDS executes a wavefront's instructions in
+// order, so the sums are formed in program order as before.
 __device__ __forceinline__ void lds_accumulate4(float *slot4, const float (&tv)[4], bool pred)
 {
     if (pred) {
-        f32x4 cur = *(f32x4 *)slot4;
-        cur[0] += tv[0]; cur[1] += tv[1]; cur[2] += tv[2]; cur[3] += tv[3];
-        *(f32x4 *)slot4 = cur;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) (void)atomicAdd(slot4 + e, tv[e]); // ds_add_f32: the result is not asked for
     }
 }
 
