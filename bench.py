@@ -166,7 +166,24 @@ def main() -> int:
     t_sel = timed(lambda: ctx.qrm_select_tiles_variance(d_img, N, cfg.H, cfg.W, cfg.tile, cfg.tile // 2, sel_off,
                                                         None, stream=stream))
     sel_bytes = N * (3 * cfg.H * cfg.W + 8)
+    # fused pre-processing from raw 2H x 2W interleaved images: the whole image, and only each image's tile
+    n_raw = min(N, 2048)
+    raw = torch.randint(0, 256, (n_raw, 2 * cfg.H, 2 * cfg.W, 3), dtype=torch.uint8, device="cuda")
+    pre_full = torch.empty((n_raw, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
+    pre_tile = torch.empty((n_raw, 3, cfg.tile, cfg.tile), dtype=torch.uint8, device="cuda")
+    t_pre_full = timed(lambda: ctx.qrm_preprocess(raw, n_raw, 2 * cfg.H, 2 * cfg.W, cfg.H, None, 0, pre_full, stream=stream))
+    t_pre_tile = timed(lambda: ctx.qrm_preprocess(raw, n_raw, 2 * cfg.H, 2 * cfg.W, cfg.H, d_off, cfg.tile, pre_tile,
+                                                  stream=stream))
+    pre_full_bytes = n_raw * (4 * 3 * cfg.H * cfg.W + 3 * cfg.H * cfg.W)
+    pre_tile_bytes = n_raw * (4 * 3 * l2 + 3 * l2 + 8)
+    del raw, pre_full, pre_tile
     stages = {
+        "preprocess_whole_image": {"us": round(t_pre_full * 1e6, 2), "images_per_s": round(n_raw / t_pre_full, 0),
+                                   "algorithmic_GBs": round(pre_full_bytes / t_pre_full / 1e9, 1),
+                                   "frac_hbm": round(pre_full_bytes / t_pre_full / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},
+        "preprocess_tile_only": {"us": round(t_pre_tile * 1e6, 2), "images_per_s": round(n_raw / t_pre_tile, 0),
+                                 "algorithmic_GBs": round(pre_tile_bytes / t_pre_tile / 1e9, 1),
+                                 "frac_hbm": round(pre_tile_bytes / t_pre_tile / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},
         "select_tiles_variance": {"us": round(t_sel * 1e6, 2), "images_per_s": round(N / t_sel, 0),
                                   "algorithmic_GBs": round(sel_bytes / t_sel / 1e9, 1),
                                   "frac_hbm": round(sel_bytes / t_sel / 1e9 / PEAK_HBM_GBS, 4), "images": N},

@@ -131,6 +131,26 @@ QRM_API qrm_status qrm_extract_tiles(qrm_ctx *ctx, const uint8_t *d_images, int6
                              const int32_t *d_off_yx, int32_t tile, uint8_t *d_tiles, void *stream);
 
 /*
+ * Fused pre-processing (Table 1: resizeto(x), centercrop(x), toTensor; Appendix A "Kernel Fusion for
+ * Preprocessing": the raw buffer is consumed in one pass).  Normalisation is not done here: the
+ * extractor's first convolution applies it.
+ * d_raw u8 [N,H_in,W_in,3], interleaved colours (a decoded image buffer); all images of a call have
+ * the same size.  The shorter side is resized to `size`, the longer one to floor(size * long / short);
+ * bilinear, pixel centres at half-integers, no anti-aliasing filter, source coordinates clamped to the
+ * image; the centre size x size window starts at ((H_r - size) / 2, (W_r - size) / 2) (integer division).
+ * Fixed point: the fraction of a source coordinate is rounded to 11 bits (w1 = round(frac * 2048),
+ * w0 = 2048 - w1), the four products pixel * wy * wx are summed exactly, then (sum + 2^21) >> 22.
+ * tile = 0: d_out u8 [N,3,size,size], the whole pre-processed image (input of qrm_detect).
+ * tile > 0: d_out u8 [N,3,tile,tile], only the tile at d_off_yx i32 [N,2] (NULL = origin 0,0; clamped
+ * to [0, size - tile]) of that image (input of qrm_extractor_forward); the rest is never computed.
+ * Errors: QRM_E_INVALID (sizes <= 0, tile > size, NULL pointer), QRM_E_UNSUPPORTED (a raw or resized
+ * side above 16384, a window wider than 1024).
+ */
+QRM_API qrm_status qrm_preprocess(qrm_ctx *ctx, const uint8_t *d_raw, int64_t N, int32_t H_in, int32_t W_in,
+                                  int32_t size, const int32_t *d_off_yx, int32_t tile, uint8_t *d_out,
+                                  void *stream);
+
+/*
  * Variance-based tile selection (Listing 1, the user-defined strategy `select_patch`): windows of
  * tile x tile pixels at `stride` (the listing: 64 and 32), the variance of every window per channel,
  * summed over the channels; the window with the largest sum is the image's tile.  Readings: argmax over

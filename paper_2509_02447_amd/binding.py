@@ -38,7 +38,7 @@ class _RsDesc(C.Structure):
 
 
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
-           "qrm_extract_tiles", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
+           "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
            "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
            "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
 
@@ -69,6 +69,8 @@ def load_library():
     lib.qrm_workspace_bytes.restype = C.c_size_t
     lib.qrm_extract_tiles.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
     lib.qrm_extract_tiles.restype = C.c_int
+    lib.qrm_preprocess.argtypes = [vp, vp, i64, i32, i32, i32, vp, i32, vp, vp]
+    lib.qrm_preprocess.restype = C.c_int
     lib.qrm_select_tiles_variance.argtypes = [vp, vp, i64, i32, i32, i32, i32, vp, vp, vp]
     lib.qrm_select_tiles_variance.restype = C.c_int
     lib.qrm_extractor_forward.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
@@ -220,6 +222,10 @@ class Context:
     def qrm_extract_tiles(self, d_images, N, H, W, d_off_yx, tile, d_tiles, stream=None):
         self._check(self._lib.qrm_extract_tiles(self._h, _dptr(d_images), int(N), int(H), int(W), _dptr(d_off_yx),
                                                 int(tile), _dptr(d_tiles), _stream_handle(stream)))
+
+    def qrm_preprocess(self, d_raw, N, H_in, W_in, size, d_off_yx, tile, d_out, stream=None):
+        self._check(self._lib.qrm_preprocess(self._h, _dptr(d_raw), int(N), int(H_in), int(W_in), int(size),
+                                             _dptr(d_off_yx), int(tile), _dptr(d_out), _stream_handle(stream)))
 
     def qrm_select_tiles_variance(self, d_images, N, H, W, tile, stride, d_off_yx, d_scores=None, stream=None):
         self._check(self._lib.qrm_select_tiles_variance(self._h, _dptr(d_images), int(N), int(H), int(W), int(tile),

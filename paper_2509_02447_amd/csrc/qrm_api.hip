@@ -704,6 +704,25 @@ qrm_status qrm_extract_tiles(qrm_ctx *c, const uint8_t *d_images, int64_t N, int
     return QRM_OK;
 }
 
+qrm_status qrm_preprocess(qrm_ctx *c, const uint8_t *d_raw, int64_t N, int32_t H_in, int32_t W_in, int32_t size,
+                          const int32_t *d_off_yx, int32_t tile, uint8_t *d_out, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
+    if (H_in <= 0 || W_in <= 0 || size <= 0 || tile < 0 || tile > size)
+        return fail(c, QRM_E_INVALID, "need H_in, W_in, size > 0 and 0 <= tile <= size");
+    const int T = tile ? tile : size;
+    if (!preprocess_supported(H_in, W_in, size, T))
+        return fail(c, QRM_E_UNSUPPORTED, "raw and resized sides up to 16384, windows up to 1024 columns");
+    if (N == 0) return QRM_OK;
+    if (!d_raw || !d_out) return fail(c, QRM_E_INVALID, "d_raw / d_out is NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    e = launch_preprocess(d_raw, N, H_in, W_in, size, tile ? d_off_yx : nullptr, T, d_out, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(c, e, "preprocess launch");
+    return QRM_OK;
+}
+
 qrm_status qrm_select_tiles_variance(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
                                      int32_t tile, int32_t stride, int32_t *d_off_yx, double *d_scores, void *stream)
 {

@@ -128,6 +128,12 @@ bool select_tiles_supported(int H, int W, int win, int stride);
 hipError_t launch_select_tiles_variance(const uint8_t *img, int64_t N, int H, int W, int win, int stride,
                                         const double w[3], int32_t *off_yx, double *scores, hipStream_t s);
 
+// Fused pre-processing: raw u8 [N,H_in,W_in,3] -> resize (shorter side x) -> centre crop x -> planar u8
+// [N,3,T,T], the whole crop (T = x) or a tile of it at off (device [N,2] or null).
+bool preprocess_supported(int H_in, int W_in, int x, int T);
+hipError_t launch_preprocess(const uint8_t *raw, int64_t N, int H_in, int W_in, int x, const int32_t *off, int T,
+                             uint8_t *out, hipStream_t s);
+
 // host-side helpers
 uint16_t f32_to_bf16_rne(float f);
 

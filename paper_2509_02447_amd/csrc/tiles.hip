@@ -3,6 +3,7 @@
 // block per (image, plane); when everything is 4-byte friendly each lane assembles one aligned output
 // dword from two aligned input dwords (funnel shift by the source misalignment), otherwise bytes.
 // Also here: variance-based tile selection (further down).
+#include <algorithm>
 #include "qrm_internal.h"
 
 namespace qrm {
@@ -185,7 +186,147 @@ __global__ __launch_bounds__(256) void tile_variance_kernel(const uint8_t *__res
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Fused pre-processing (Table 1 of the paper: resize to x, centre crop x, to tensor; Appendix A: one pass
+// from the raw buffer): raw u8 images, height x width x 3 interleaved, -> planar u8 [3][T][T], where the
+// T x T window is either the whole centre crop (T = x) or one tile of it at a per-image origin: only the
+// source pixels under that window are touched.  Bilinear, pixel centres at half-integers, fixed point:
+// the fraction of a source coordinate is rounded to 11 bits, the four products are exact integers, the
+// sum is rounded half up (>> 22).  Integer arithmetic only: the bytes do not depend on the hardware.
+//
+// One workgroup per (image, strip of rows).  The column taps of the window are computed once into LDS
+// (two integer divisions per column), a lane then produces four neighbouring pixels of a row for the
+// three colours and writes one dword per plane.
+// ------------------------------------------------------------------------------------------------
+constexpr int kCoefBits = 11;
+constexpr int kMaxTile = 1024; // columns of a window
+
+struct PreArgs {
+    int H_in, W_in, x, T;  // raw size, size after resize + crop, window
+    int Hr, Wr, cy, cx;    // resized size, origin of the centre crop in it
+    int rows_per_block;
+};
+
+__device__ __forceinline__ void source_taps(int dst, int n_in, int n_res, int &i0, int &i1, int &w1)
+{
+    int num = (2 * dst + 1) * n_in - n_res; // numerator of the source coordinate over 2 * n_res
+    const int den = 2 * n_res;
+    num = num < 0 ? 0 : num;
+    i0 = num / den;
+    int a = num - i0 * den;
+    if (i0 >= n_in - 1) {
+        i0 = n_in - 1;
+        a = 0;
+    }
+    i1 = min(i0 + 1, n_in - 1);
+    w1 = (a * (1 << kCoefBits) + n_res) / den; // round(fraction * 2048)
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restrict__ raw, PreArgs a,
+                                                         const int32_t *__restrict__ off, uint8_t *__restrict__ out)
+{
+    __shared__ int s_x0[kMaxTile], s_x1[kMaxTile];
+    __shared__ uint16_t s_w1[kMaxTile];
+    const int tid = threadIdx.x;
+    const int64_t n = blockIdx.x;
+    int oy = 0, ox = 0;
+    if (off && a.T < a.x) {
+        oy = clampi(off[2 * n], 0, a.x - a.T);
+        ox = clampi(off[2 * n + 1], 0, a.x - a.T);
+    }
+    for (int t = tid; t < a.T; t += 256) {
+        int i0, i1, w1;
+        source_taps(a.cx + ox + t, a.W_in, a.Wr, i0, i1, w1);
+        s_x0[t] = i0 * 3; // byte offsets within a raw row
+        s_x1[t] = i1 * 3;
+        s_w1[t] = (uint16_t)w1;
+    }
+    __syncthreads();
+    const uint8_t *img = raw + n * (int64_t)a.H_in * a.W_in * 3;
+    uint8_t *dst = out + n * 3 * (int64_t)a.T * a.T;
+    const int r_begin = blockIdx.y * a.rows_per_block, r_end = min(a.T, r_begin + a.rows_per_block);
+    const int groups = a.T / VEC; // pixel groups per row
+    const int64_t plane = (int64_t)a.T * a.T;
+    for (int idx = tid; idx < (r_end - r_begin) * groups; idx += 256) {
+        const int ty = r_begin + idx / groups, tx = (idx % groups) * VEC;
+        int y0, y1, wy1;
+        source_taps(a.cy + oy + ty, a.H_in, a.Hr, y0, y1, wy1);
+        const int wy0 = (1 << kCoefBits) - wy1;
+        const uint8_t *row0 = img + (int64_t)y0 * a.W_in * 3, *row1 = img + (int64_t)y1 * a.W_in * 3;
+        uint32_t pk[3] = {0u, 0u, 0u};
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+            const int b0 = s_x0[tx + v], b1 = s_x1[tx + v];
+            const int wx1 = s_w1[tx + v], wx0 = (1 << kCoefBits) - wx1;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                const int top = row0[b0 + c] * wx0 + row0[b1 + c] * wx1; // < 2^19
+                const int bot = row1[b0 + c] * wx0 + row1[b1 + c] * wx1;
+                const uint32_t s = (uint32_t)(top * wy0 + bot * wy1);    // <= 255 * 2^22 < 2^30
+                const uint32_t val = (s + (1u << (2 * kCoefBits - 1))) >> (2 * kCoefBits);
+                pk[c] |= val << (8 * v);
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            uint8_t *p = dst + c * plane + (int64_t)ty * a.T + tx;
+            if (VEC == 4) *(uint32_t *)p = pk[c];
+            else *p = (uint8_t)pk[c];
+        }
+    }
+}
+
 } // namespace
+
+void preprocess_resized_shape(int H_in, int W_in, int x, int *Hr, int *Wr)
+{
+    if (H_in <= W_in) {
+        *Hr = x;
+        *Wr = (int)std::max<int64_t>(x, (int64_t)x * W_in / H_in);
+    } else {
+        *Hr = (int)std::max<int64_t>(x, (int64_t)x * H_in / W_in);
+        *Wr = x;
+    }
+}
+
+bool preprocess_supported(int H_in, int W_in, int x, int T)
+{
+    if (H_in <= 0 || W_in <= 0 || x <= 0 || T <= 0 || T > x || T > kMaxTile) return false;
+    if (H_in > 16384 || W_in > 16384) return false;
+    int Hr, Wr;
+    preprocess_resized_shape(H_in, W_in, x, &Hr, &Wr);
+    // (2 * dst + 1) * n_in and fraction * 2048 must stay below 2^31
+    return Hr <= 16384 && Wr <= 16384 && (int64_t)(2 * (int64_t)std::max(Hr, Wr) + 1) * std::max(H_in, W_in) < (1LL << 31) &&
+           (int64_t)2 * std::max(Hr, Wr) * 2048 < (1LL << 31);
+}
+
+hipError_t launch_preprocess(const uint8_t *raw, int64_t N, int H_in, int W_in, int x, const int32_t *off, int T,
+                             uint8_t *out, hipStream_t s)
+{
+    if (N <= 0) return hipSuccess;
+    PreArgs a{};
+    a.H_in = H_in; a.W_in = W_in; a.x = x; a.T = T;
+    preprocess_resized_shape(H_in, W_in, x, &a.Hr, &a.Wr);
+    a.cy = (a.Hr - x) / 2;
+    a.cx = (a.Wr - x) / 2;
+    // enough workgroups for the chip when there are few images, few column-tap computations otherwise
+    int strips = (int)std::min<int64_t>((T + 7) / 8, std::max<int64_t>(1, 2048 / N));
+    a.rows_per_block = (T + strips - 1) / strips;
+    strips = (T + a.rows_per_block - 1) / a.rows_per_block;
+    const bool vec = T % 4 == 0 && ((uintptr_t)out & 3u) == 0;
+    const int64_t kMaxGrid = 1LL << 30;
+    for (int64_t n0 = 0; n0 < N; n0 += kMaxGrid) {
+        const int64_t cnt = N - n0 < kMaxGrid ? N - n0 : kMaxGrid;
+        const uint8_t *raw0 = raw + n0 * (int64_t)H_in * W_in * 3;
+        const int32_t *off0 = off ? off + 2 * n0 : nullptr;
+        uint8_t *out0 = out + n0 * 3 * (int64_t)T * T;
+        const dim3 grid((unsigned)cnt, (unsigned)strips);
+        if (vec) hipLaunchKernelGGL(preprocess_kernel<4>, grid, dim3(256), 0, s, raw0, a, off0, out0);
+        else hipLaunchKernelGGL(preprocess_kernel<1>, grid, dim3(256), 0, s, raw0, a, off0, out0);
+    }
+    return hipGetLastError();
+}
 
 bool select_tiles_supported(int H, int W, int win, int stride)
 {

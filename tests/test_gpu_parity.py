@@ -423,6 +423,83 @@ def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
 
 # ---------------------------------------------------------------- error paths (host side only)
 
+# ---------------------------------------------------------------- fused pre-processing
+
+from oracle import preprocess as pre_oracle
+
+PRE_CASES = [  # N, H_in, W_in, size, tile (0 = whole image)
+    (2, 512, 512, 256, 64),     # the benchmark's shape: 512 x 512 raw -> 256 x 256 -> one 64 x 64 tile
+    (1, 300, 420, 128, 0),      # landscape, whole image
+    (3, 77, 50, 40, 0),         # portrait, odd sizes
+    (3, 60, 60, 60, 20),        # identity size: the tile is a window of the raw image
+    (2, 40, 56, 90, 32),        # enlarging
+    (4, 333, 500, 96, 31),      # tile width not a multiple of 4: byte stores
+    (2, 1024, 768, 256, 128),
+]
+
+
+@pytest.mark.parametrize("N,H_in,W_in,size,tile", PRE_CASES)
+def test_preprocess_bit_exact(qrm, N, H_in, W_in, size, tile):
+    rng = np.random.default_rng(H_in + 3 * W_in + size)
+    raw = rng.integers(0, 256, size=(N, H_in, W_in, 3), dtype=np.uint8)
+    off = None
+    if tile:
+        off = rng.integers(-5, size - tile + 6, size=(N, 2)).astype(np.int32)     # some outside: clamped
+        off[0] = (size - tile, 0)
+    ref = pre_oracle.preprocess(raw, size, off, tile)
+    ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
+    T = tile if tile else size
+    d_out = empty((N, 3, T, T), torch.uint8)
+    ctx.qrm_preprocess(dev(raw), N, H_in, W_in, size, None if off is None else dev(off), tile, d_out)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_out.cpu().numpy(), ref)
+    if tile:    # no origins given: the top-left tile
+        ctx.qrm_preprocess(dev(raw), N, H_in, W_in, size, None, tile, d_out)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_out.cpu().numpy(), pre_oracle.preprocess(raw, size, np.zeros((N, 2), np.int32), tile))
+    ctx.close()
+
+
+def test_preprocess_tile_then_extractor_equals_oracle_path(qrm):
+    """Raw 512 x 512 images -> (resize, crop, tile) in one kernel -> extractor, against the oracle's chain."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = 6
+    rng = np.random.default_rng(12)
+    raw = rng.integers(0, 256, size=(N, 512, 512, 3), dtype=np.uint8)
+    off = synth.offsets(cfg, 0, N)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    d_tiles = empty((N, 3, cfg.tile, cfg.tile), torch.uint8)
+    ctx.qrm_preprocess(dev(raw), N, 512, 512, cfg.H, dev(off), cfg.tile, d_tiles)
+    d_logits, d_bits = empty((N, cfg.n_bits), torch.float32), empty((N, cfg.n_bits), torch.uint8)
+    ctx.qrm_extractor_forward(d_tiles, N, cfg.tile, cfg.tile, d_logits, d_bits)
+    torch.cuda.synchronize()
+    tiles = pre_oracle.preprocess(raw, cfg.H, off, cfg.tile)
+    assert np.array_equal(d_tiles.cpu().numpy(), tiles)
+    ref_logits, _ = oracle.extractor_forward(wts, tiles)
+    check_logits(d_logits.cpu().numpy(), ref_logits, d_bits.cpu().numpy(), what="pre-processed tiles -> extractor")
+    # the whole pre-processed image followed by the stand-alone tile crop gives the same tiles
+    d_full = empty((N, 3, cfg.H, cfg.W), torch.uint8)
+    ctx.qrm_preprocess(dev(raw), N, 512, 512, cfg.H, None, 0, d_full)
+    d_t2 = empty((N, 3, cfg.tile, cfg.tile), torch.uint8)
+    ctx.qrm_extract_tiles(d_full, N, cfg.H, cfg.W, dev(off), cfg.tile, d_t2)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_t2.cpu().numpy(), tiles)
+    ctx.close()
+
+
+def test_preprocess_error_statuses(qrm):
+    ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
+    d_raw, d_out = empty((1, 32, 32, 3), torch.uint8), empty((1, 3, 16, 16), torch.uint8)
+    for args in ((0, 32, 16, 0), (32, 32, 0, 0), (32, 32, 16, 17), (32, 32, 16, -1), (20000, 32, 16, 0)):
+        with pytest.raises(qrm.QrmError):
+            ctx.qrm_preprocess(d_raw, 1, args[0], args[1], args[2], None, args[3], d_out)
+    with pytest.raises(qrm.QrmError):
+        ctx.qrm_preprocess(None, 1, 32, 32, 16, None, 0, d_out)
+    ctx.qrm_preprocess(d_raw, 0, 32, 32, 16, None, 0, d_out)     # empty batch
+    ctx.close()
+
+
 # ---------------------------------------------------------------- variance-based tile selection
 
 from oracle import tileselect
