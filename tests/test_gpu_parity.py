@@ -310,6 +310,30 @@ def test_detect_config_c2_sample(qrm, policy):
     ctx.close()
 
 
+def test_detect_config_c2_full_size_sampled(qrm):
+    """The whole tiled-detection configuration (4096 images) in the launch configuration the benchmark times
+    (default micro-batch): extractor outputs of a sample of images against the oracle, one by one - the first and
+    last image, both sides of every micro-batch boundary, and a random draw -, the Reed-Solomon outputs of ALL
+    images against the oracle's decoder on the device's own hard bits, and bits = (logit > 0) everywhere."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N = cfg.n_images
+    imgs, off = synth.images(cfg, 0, N), synth.offsets(cfg, 0, N)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    got = run_detect(ctx, cfg, imgs, off)
+    ctx.close()
+    assert np.isfinite(got["logits"]).all()
+    assert np.array_equal(got["bits"], (got["logits"] > 0).astype(np.uint8))
+    syms = oracle.bits_to_symbols(got["bits"], cfg.m)
+    om, oc, oe = oracle.rs_decode(syms, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    assert np.array_equal(got["msg"], om) and np.array_equal(got["codeword"], oc) and np.array_equal(got["nerr"], oe)
+    rng = np.random.default_rng(2)
+    sample = sorted(set([0, 1, 255, 256, 1022, 1023, 1024, 1025, 2047, 2048, 3071, 3072, N - 2, N - 1] +
+                        rng.integers(0, N, size=18).tolist()))
+    ref = oracle.detect(wts, imgs[sample], off[sample], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    check_logits(got["logits"][sample], ref["logits"], got["bits"][sample], what=f"C2 full size, {len(sample)} sampled images")
+
+
 def test_detect_config_c4_sample(qrm):
     cfg = synth.CONFIGS["C4"]
     wts = synth.config_weights(cfg)
