@@ -782,20 +782,30 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     const float ka[3] = {src.inv_std[0] * (1.0f / 255.0f), src.inv_std[1] * (1.0f / 255.0f), src.inv_std[2] * (1.0f / 255.0f)};
     const float kb[3] = {-src.mean[0] * src.inv_std[0], -src.mean[1] * src.inv_std[1], -src.mean[2] * src.inv_std[2]};
     const int plane = src.H * src.W;
-    auto pixel_fetch = [&](const uint8_t *tile0, int y0, int e, bool &inside) -> uint8_t {
-        const int row = e / kRowElems, rem = e - row * kRowElems;
+    // The load is unconditional (coordinates clamped into the tile, the value dropped later when it lies
+    // outside) and fetches the aligned dword that holds the byte (it never leaves the byte's page): a load under
+    // a lane mask, or a byte load with its widening, would be waited for on the spot, and a step would then
+    // contain two round trips to memory instead of hiding them behind its matrix work.
+    auto pixel_fetch = [&](const uint8_t *tile0, int y0, int e, bool &inside, uint32_t &shift) -> uint32_t {
+        const int ec = min(e, 2 * kRowElems - 1);
+        const int row = ec / kRowElems, rem = ec - row * kRowElems;
         const int c = rem / kHaloW, col = rem - c * kHaloW;
         const int ty = y0 + row, tx = col - 1;
         inside = e < 2 * kRowElems && ty >= 0 && ty < g.h && tx >= 0 && tx < g.w;
-        return inside ? tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx] : (uint8_t)0;
+        const int tyc = clampi(ty, 0, g.h - 1), txc = clampi(tx, 0, g.w - 1);
+        const uintptr_t p = (uintptr_t)(tile0 + ((int64_t)c * plane + (int64_t)tyc * src.W + txc));
+        shift = (uint32_t)(p & 3u) * 8u;
+        typedef const uint32_t __attribute__((address_space(1))) *global_word_t; // a global load, not a flat one
+        return *(global_word_t)(p & ~(uintptr_t)3);
     };
-    auto pixel_store = [&](int y0, int e, uint8_t v, bool inside) { // y0: place of the first row in the stream of images
+    auto pixel_store = [&](int y0, int e, uint32_t word, uint32_t shift, bool inside) { // y0: place of the first row in the stream of images
+        asm volatile("" : "+v"(word)); // the value is first looked at here, not where it was asked for
         if (e < 2 * kRowElems) {
             const int row = e / kRowElems, rem = e - row * kRowElems;
             const int c = rem / kHaloW, col = rem - c * kHaloW;
             const float a = c == 0 ? ka[0] : (c == 1 ? ka[1] : ka[2]);
             const float b = c == 0 ? kb[0] : (c == 1 ? kb[1] : kb[2]);
-            const float f = inside ? fmaf((float)v, a, b) : 0.f;
+            const float f = inside ? fmaf((float)((word >> shift) & 0xffu), a, b) : 0.f;
             s_pix[slot_of(y0 + row)][col][c] = __builtin_bit_cast(uint16_t, (bf16_t)f);
         }
     };
@@ -861,8 +871,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     bool inside;
-                    const uint8_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside);
-                    pixel_store(y0, tid + 256 * k, v, inside);
+                    uint32_t shift;
+                    const uint32_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside, shift);
+                    pixel_store(y0, tid + 256 * k, v, shift, inside);
                 }
         }
     } else {
@@ -953,7 +964,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             const int pxl = ln & 31, hf = ln >> 5;
             const int x = xb * 32 + pxl;
             // FIRST: the raw pixels of virtual rows 2sg+3, 2sg+4 (window of step sg+1) start their way into registers
-            uint8_t pv[2] = {0, 0};
+            uint32_t pv[2] = {0, 0}, psh[2] = {0, 0};
             bool pin[2] = {false, false};
             bool fetch = false;
             if (FIRST && p1.i < n_cnt) {
@@ -966,7 +977,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
                 if (fetch) {
 #pragma unroll
-                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, y0, tid + 256 * k, pin[k]);
+                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, y0, tid + 256 * k, pin[k], psh[k]);
                 }
             }
             if (pa.i < n_cnt && pa.s < S) {
@@ -1032,6 +1043,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                             (u32x4){0u, 0u, 0u, 0u};
                 if (!FIRST && pa.i + 1 < n_cnt) prepare_init(n_begin + pa.i + 1); // nobody reads s_initA in this step
             }
+            if (FIRST && fetch) { // their slots were last read two steps ago; before the stores below, which need not be waited for
+#pragma unroll
+                for (int k = 0; k < 2; ++k) pixel_store(2 * sg + 3, tid + 256 * k, pv[k], psh[k], pin[k]);
+            }
             if (FIRST && fin) { // the rows group B accumulated in the previous step
                 const float *srcx = &s_accx[((((sg - 3) & 1) * 4 + w4) * 8) * 256 + ln * 4];
                 f32x16 a[RW];
@@ -1043,10 +1058,6 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         a[r][4 * q] = v[0]; a[r][4 * q + 1] = v[1]; a[r][4 * q + 2] = v[2]; a[r][4 * q + 3] = v[3];
                     }
                 finish(a, n_begin + pf.i, pf.s);
-            }
-            if (FIRST && fetch) { // their slots were last read two steps ago
-#pragma unroll
-                for (int k = 0; k < 2; ++k) pixel_store(2 * sg + 3, tid + 256 * k, pv[k], pin[k]);
             }
         } else {
             const int ln = pin_in_loop(tid & 63);
