@@ -39,7 +39,7 @@ def main() -> int:
     ap.add_argument("--config", default="C2", help="C2 (headline), C3 or C4")
     ap.add_argument("--images", type=int, default=0, help="override the number of images (0 = the configuration's)")
     ap.add_argument("--micro-batch", type=int, default=0)
-    ap.add_argument("--cpu-sample", type=int, default=48, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=256, help="images the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--policy", default="random", choices=["random", "random_grid", "fixed"])
     ap.add_argument("--chunks", type=int, default=16, help="C5 only: chunks per step (a full C5 pass is 128)")
     ap.add_argument("--chunk-images", type=int, default=8192, help="C5 only: images per pinned host chunk")
