@@ -1081,12 +1081,15 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         // date from the start of this step) is done, then the rows needed two steps from now are put on
         // their way, one row per group: rows 2s+1, 2s+2 of the image of step sg + 2, or rows -1, 0 of the
         // image after it when that step is the one of the padding rows.
-        if (!FIRST) {
+        if (!FIRST && grp == 0) { // group A has time to spare at the end of a step, group B is the critical path
             __builtin_amdgcn_s_waitcnt(kWaitVm0);
             if (pl.i < n_cnt) {
                 const bool nxt = pl.s == S;
                 const int li = pl.i + (nxt ? 1 : 0);
-                if (li < n_cnt) issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1) + grp, 2 * sg + 5 + grp);
+                if (li < n_cnt) {
+                    issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1), 2 * sg + 5);
+                    issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1) + 1, 2 * sg + 6);
+                }
             }
         }
         lds_barrier();
