@@ -125,6 +125,7 @@ def main() -> int:
                                                                  and not args.images) else None,
                 "launches": int(k_launches), "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),
                 "flops_per_launch": k_flops / max(1, k_launches),
+                "sustained_on_random_data": None,   # filled in below: pure matrix loop on random operands
                 "timing": "HIP events around every launch, second pass of the same steps"}
 
     # ---- the other two stages on their own (HBM-bound by bytes, in practice latency / ALU bound)
@@ -188,7 +189,15 @@ def main() -> int:
     pre_full_bytes = n_raw * (4 * 3 * cfg.H * cfg.W + 3 * cfg.H * cfg.W)
     pre_tile_bytes = n_raw * (4 * 3 * l2 + 3 * l2 + 8)
     del raw, pre_full, pre_tile
+    # what the matrix pipes sustain with nothing else running, by operand data (the clock follows the power budget)
+    matrix_probe = {"zeros_tflops": round(ctx.qrm_matrix_rate_probe(0), 1),
+                    "random_data_tflops": round(ctx.qrm_matrix_rate_probe(2), 1),
+                    "note": "back-to-back bf16 32x32x16 matrix instructions, 8 wavefronts per CU, no memory traffic"}
+    if isinstance(roofline, dict) and roofline.get("bound") == "mfma":
+        roofline["sustained_on_random_data"] = {"tflops": matrix_probe["random_data_tflops"],
+                                                 "frac_of_it": round(roofline["achieved"] / matrix_probe["random_data_tflops"], 4)}
     stages = {
+        "matrix_pipe_probe": matrix_probe,
         "preprocess_whole_image": {"us": round(t_pre_full * 1e6, 2), "images_per_s": round(n_raw / t_pre_full, 0),
                                    "algorithmic_GBs": round(pre_full_bytes / t_pre_full / 1e9, 1),
                                    "frac_hbm": round(pre_full_bytes / t_pre_full / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},

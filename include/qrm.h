@@ -280,6 +280,17 @@ QRM_API qrm_status qrm_profile_enable(qrm_ctx *ctx, int32_t on);
 QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, double *ms_total, int64_t *launches, double *flops,
                                     int32_t *blocks_per_launch);
 
+/*
+ * Diagnostic for benchmarks: the rate the matrix pipes sustain when nothing else runs - eight wavefronts per
+ * compute unit issuing the bf16 32x32x16 matrix instruction back to back for a few milliseconds - on operands
+ * of the given kind: data = 0 zeros, 1 one constant, 2 random (one side small normal values like weights, the
+ * other half zeros and half positive like activations after a ReLU).  The part's clock follows its power
+ * budget and the power of a matrix instruction follows its data, so the third figure, not the published
+ * peak, is what a convolution on real activations can approach.  *tflops receives 10^12 FLOP/s.
+ * Allocates and frees a small scratch buffer; synchronises the device's default stream.
+ */
+QRM_API qrm_status qrm_matrix_rate_probe(qrm_ctx *ctx, int32_t data, double *tflops);
+
 /* Library version string, e.g. "qrm 0.1 gfx950". */
 QRM_API const char *qrm_version(void);
 

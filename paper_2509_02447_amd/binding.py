@@ -40,7 +40,7 @@ class _RsDesc(C.Structure):
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
            "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
-           "qrm_profile_enable", "qrm_profile_read", "qrm_version"]
+           "qrm_profile_enable", "qrm_profile_read", "qrm_matrix_rate_probe", "qrm_version"]
 
 
 def lib_path() -> str:
@@ -96,6 +96,8 @@ def load_library():
     lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                                      C.POINTER(C.c_int32)]
     lib.qrm_profile_read.restype = C.c_int
+    lib.qrm_matrix_rate_probe.argtypes = [vp, i32, C.POINTER(C.c_double)]
+    lib.qrm_matrix_rate_probe.restype = C.c_int
     lib.qrm_version.argtypes = []
     lib.qrm_version.restype = C.c_char_p
     _lib = lib
@@ -215,6 +217,12 @@ class Context:
         ms, n, fl, bp = C.c_double(), C.c_int64(), C.c_double(), C.c_int32()
         self._check(self._lib.qrm_profile_read(self._h, C.byref(ms), C.byref(n), C.byref(fl), C.byref(bp)))
         return ms.value, n.value, fl.value, bp.value
+
+    def qrm_matrix_rate_probe(self, data: int) -> float:
+        """-> TFLOP/s the matrix pipes sustain on zeros (0), a constant (1) or random operands (2)."""
+        v = C.c_double()
+        self._check(self._lib.qrm_matrix_rate_probe(self._h, int(data), C.byref(v)))
+        return v.value
 
     def qrm_workspace_bytes(self, N: int, tile_h: int, tile_w: int) -> int:
         return int(self._lib.qrm_workspace_bytes(self._h, int(N), int(tile_h), int(tile_w)))

@@ -1636,6 +1636,39 @@ hipError_t launch_linear_pack(const float *partial, int n_part, int nbp, int64_t
     return hipGetLastError();
 }
 
+// Diagnostic: what the matrix pipes sustain with nothing else going on.  Eight wavefronts per CU issue
+// v_mfma_f32_32x32x16_bf16 back to back on four operand sets taken from `src` (8192 floats: 4096 for the A
+// side, 4096 for the B side).  The clock of the part follows its power budget, and the power of a matrix
+// instruction follows the data: zeros run at the published rate, random data do not.
+__global__ __launch_bounds__(512) void matrix_rate_kernel(const float *__restrict__ src, int iters, float *__restrict__ out)
+{
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a[s][i] = (bf16_t)src[((s * 8 + i) * 512 + threadIdx.x) % 4096];
+            b[s][i] = (bf16_t)src[((s * 8 + i) * 512 + threadIdx.x) % 4096 + 4096];
+        }
+    f32x16 acc[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[s][i] = 0.f;
+#pragma unroll 1
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc[s] = mfma32(a[s], b[s], acc[s]);
+    }
+    out[blockIdx.x * 512 + threadIdx.x] = acc[0][0] + acc[1][1] + acc[2][2] + acc[3][3];
+}
+
+hipError_t launch_matrix_rate(const float *src, int iters, int blocks, float *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(matrix_rate_kernel, dim3(blocks), dim3(512), 0, s, src, iters, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_nhwc_to_nchw(const bf16_t *in, int64_t n_img, int h, int w, int C, float *out, hipStream_t s)
 {
     const int64_t total = n_img * h * w * C;

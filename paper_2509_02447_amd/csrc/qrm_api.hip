@@ -482,6 +482,48 @@ bool build_gf_tables(int m, uint32_t poly, std::vector<uint8_t> &exp2, std::vect
 
 extern "C" {
 
+qrm_status qrm_matrix_rate_probe(qrm_ctx *c, int32_t data, double *tflops)
+{
+    if (!c) return QRM_E_INVALID;
+    if (data < 0 || data > 2 || !tflops) return fail(c, QRM_E_INVALID, "data is 0 (zeros), 1 (a constant) or 2 (random); tflops must not be NULL");
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    // operands: A side like rounded weights (normal, small), B side like activations after a ReLU
+    std::vector<float> h(8192);
+    uint64_t state = 0x9E3779B97F4A7C15ull;
+    auto uni = [&]() {
+        state = state * 6364136223846793005ull + 1442695040888963407ull;
+        return ((double)(state >> 11) + 1.0) / 9007199254740994.0;
+    };
+    for (int i = 0; i < 8192; ++i) {
+        const double n = sqrt(-2.0 * log(uni())) * cos(6.283185307179586 * uni());
+        h[i] = data == 0 ? 0.f : data == 1 ? 1.5f : (float)(i >= 4096 ? (n > 0 ? n : 0.0) : 0.06 * n);
+    }
+    const int blocks = c->num_cu, iters = 8000, reps = 3;
+    float *d_src = nullptr, *d_out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    e = hipMalloc(&d_src, h.size() * 4);
+    if (e == hipSuccess) e = hipMalloc(&d_out, (size_t)blocks * 512 * 4);
+    if (e == hipSuccess) e = hipMemcpy(d_src, h.data(), h.size() * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = launch_matrix_rate(d_src, iters, blocks, d_out, nullptr); // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_matrix_rate(d_src, iters, blocks, d_out, nullptr);
+    if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (d_src) (void)hipFree(d_src);
+    if (d_out) (void)hipFree(d_out);
+    if (e != hipSuccess) return hip_fail(c, e, "matrix rate probe");
+    const double flops = (double)reps * blocks * 8 * (double)iters * 4 * 32768.0; // 2 * 32 * 32 * 16 per instruction
+    *tflops = flops / ((double)ms * 1e-3) / 1e12;
+    return QRM_OK;
+}
+
 const char *qrm_version(void) { return "qrm 0.1 gfx950"; }
 
 const char *qrm_last_error(const qrm_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }

@@ -754,6 +754,17 @@ def test_verification_error_statuses(qrm):
     ctx.close()
 
 
+def test_matrix_rate_probe_reports_plausible_rates(qrm):
+    """The diagnostic probe: zeros run near the published rate, random operands slower, both far above zero."""
+    ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
+    zeros, rnd = ctx.qrm_matrix_rate_probe(0), ctx.qrm_matrix_rate_probe(2)
+    print(f"[probe] matrix pipes: {zeros:.0f} TFLOP/s on zeros, {rnd:.0f} TFLOP/s on random operands")
+    assert 500.0 < rnd <= zeros * 1.05 and zeros < 2700.0
+    with pytest.raises(qrm.QrmError):
+        ctx.qrm_matrix_rate_probe(3)
+    ctx.close()
+
+
 def test_error_statuses(qrm):
     cfg = synth.CONFIGS["C2"]
     wts = synth.config_weights(cfg)
