@@ -5,7 +5,7 @@
 // or a failure flag.  The paper's decoder is Berlekamp-Welch on the CPU; this kernel reaches the same
 // result through syndromes -> Berlekamp-Massey -> Chien search -> Forney.
 //
-// Mapping: a group of G lanes owns one codeword (G = 16 for n <= 16, so a 64-wide wavefront decodes
+// Mapping (group kernel; short codes use the lane-per-word kernel further down): a group of G lanes owns one codeword (G = 16 for n <= 16, so a 64-wide wavefront decodes
 // four words; G = 64 otherwise, each lane then holds ceil(n/64) symbols).  Lane i of the group holds
 // symbol i, i.e. the coefficient of x^(n-1-i).  Syndromes are XOR-reduced across the group (packed
 // four per 32-bit word), the short serial Berlekamp-Massey recursion is replicated in every lane, and
@@ -241,6 +241,198 @@ __global__ __launch_bounds__(256) void rs_decode_kernel(RsParams p, const uint8_
     }
 }
 
+// Short codes (n <= 16): one word per LANE.  The group kernel above repeats the serial recursion of
+// Berlekamp-Massey on all lanes of a word and is bound by the vector ALUs; here nothing is repeated: a lane reads
+// its word (adjacent lanes read adjacent words), forms the 2t syndromes (exponents are the same for all lanes,
+// so they live in scalar registers), runs the recursion once, evaluates the locator at the n positions, and does
+// Forney only at the (at most t) roots it found.  Same decisions, same outputs as the group kernel.
+template <int TMAX>
+__global__ __launch_bounds__(256) void rs_decode_lane_kernel(RsParams p, const uint8_t *__restrict__ sym, int64_t N,
+                                                             uint8_t *__restrict__ msg, uint8_t *__restrict__ cw,
+                                                             int8_t *__restrict__ nerr, KeyArgs key)
+{
+    constexpr int NMAX = 16;
+    __shared__ uint8_t s_exp[512];
+    __shared__ uint8_t s_log[256];
+    __shared__ uint8_t s_key[256];
+    const int tid = threadIdx.x;
+    const int ord = p.q - 1;
+    const bool with_key = key.matches != nullptr; // the same for every lane
+    for (int i = tid; i < 2 * ord; i += 256) s_exp[i] = p.exp2[i];
+    for (int i = tid; i < p.q; i += 256) s_log[i] = p.log[i];
+    s_key[tid] = (with_key && tid < p.k) ? key.key[tid] : 0;
+    __syncthreads();
+    Gf gf{s_exp, s_log, ord};
+    const int n = p.n, k = p.k, two_t = p.two_t, t = p.two_t / 2;
+    const int64_t w = (int64_t)blockIdx.x * 256 + tid;
+    if (w >= N) return; // no cross-lane operation below
+    const uint8_t *src = sym + w * n;
+
+    // ---- symbols and syndromes
+    int r[NMAX];
+    int S[2 * TMAX];
+#pragma unroll
+    for (int j = 0; j < 2 * TMAX; ++j) S[j] = 0;
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) {
+        r[i] = 0;
+        if (i < n) {
+            const int v = src[i] & (p.q - 1);
+            r[i] = v;
+            const int pw = n - 1 - i;       // this symbol multiplies x^pw, pw < ord
+            int e = (p.fcr * pw) % ord;     // exponent of alpha^(fcr*pw): the same in every lane
+            const int lv = s_log[v];
+#pragma unroll
+            for (int j = 0; j < 2 * TMAX; ++j) {
+                if (j < two_t) S[j] ^= v ? s_exp[lv + e] : 0;
+                e += pw;
+                if (e >= ord) e -= ord;
+            }
+        }
+    }
+
+    // ---- Berlekamp-Massey
+    int Lam[TMAX + 1], Bp[TMAX + 1];
+#pragma unroll
+    for (int i = 0; i <= TMAX; ++i) { Lam[i] = (i == 0); Bp[i] = (i == 0); }
+    int L = 0;
+#pragma unroll
+    for (int rr = 0; rr < 2 * TMAX; ++rr) {
+        if (rr < two_t) {
+            int d = S[rr];
+#pragma unroll
+            for (int i = 1; i <= TMAX; ++i)
+                if (i <= rr && i <= L) d ^= gf.mul(Lam[i], S[rr - i]);
+            int xB[TMAX + 1];
+            xB[0] = 0;
+#pragma unroll
+            for (int i = 1; i <= TMAX; ++i) xB[i] = Bp[i - 1];
+            const bool grow = d != 0 && 2 * L <= rr;
+            const int dinv = d ? gf.inv(d) : 0;
+#pragma unroll
+            for (int i = 0; i <= TMAX; ++i) {
+                const int old = Lam[i];
+                Lam[i] = old ^ gf.mul(d, xB[i]);              // d = 0: unchanged
+                Bp[i] = grow ? gf.mul(dinv, old) : xB[i];
+            }
+            if (grow) L = rr + 1 - L;
+        }
+    }
+    bool fail = L > t;
+    {
+        int top = 0;
+#pragma unroll
+        for (int i = 1; i <= TMAX; ++i)
+            if (i == L) top = Lam[i];
+        if (L > 0 && L <= t && top == 0) fail = true;
+    }
+
+    // ---- Omega = S(x) Lam(x) mod x^(2t)
+    int Om[2 * TMAX];
+#pragma unroll
+    for (int i = 0; i < 2 * TMAX; ++i) {
+        int o = 0;
+#pragma unroll
+        for (int j = 0; j <= TMAX; ++j)
+            if (j <= i && j <= L) o ^= gf.mul(Lam[j], S[i - j]);
+        Om[i] = (i < two_t) ? o : 0;
+    }
+
+    // ---- Chien search over the n positions (exponents are the same in every lane), roots remembered
+    int lamlog[TMAX + 1];
+#pragma unroll
+    for (int j = 1; j <= TMAX; ++j) lamlog[j] = s_log[Lam[j]];
+    int nroots = 0;
+    int rootpos[TMAX];
+#pragma unroll
+    for (int q2 = 0; q2 < TMAX; ++q2) rootpos[q2] = 0;
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) {
+        if (i < n) {
+            const int pw = n - 1 - i;
+            const int xe = pw == 0 ? 0 : ord - pw; // exponent of X^-1 = alpha^-pw
+            int lam_x = Lam[0];
+            int e = 0;
+#pragma unroll
+            for (int j = 1; j <= TMAX; ++j) {
+                e += xe;
+                if (e >= ord) e -= ord;
+                if (j <= L && Lam[j]) lam_x ^= s_exp[lamlog[j] + e];
+            }
+            const bool root = !fail && L > 0 && lam_x == 0;
+            if (root) {
+#pragma unroll
+                for (int q2 = 0; q2 < TMAX; ++q2)
+                    if (q2 == nroots) rootpos[q2] = i;
+                ++nroots;
+            }
+        }
+    }
+    if (nroots != L) fail = true;
+
+    // ---- Forney at the roots
+    int evpos[TMAX], evval[TMAX];
+#pragma unroll
+    for (int q2 = 0; q2 < TMAX; ++q2) {
+        evpos[q2] = -1;
+        evval[q2] = 0;
+        if (!fail && q2 < nroots && q2 < L) {
+            const int i = rootpos[q2];
+            const int pw = n - 1 - i;
+            const int xe = pw == 0 ? 0 : ord - pw;
+            int num = Om[0], den = 0;
+            int e = 0;
+#pragma unroll
+            for (int j = 1; j < 2 * TMAX; ++j) {
+                e += xe;
+                if (e >= ord) e -= ord;
+                if (j < two_t) num ^= gf.mul_pow(Om[j], e);
+            }
+            e = 0;
+#pragma unroll
+            for (int j = 1; j <= TMAX; ++j) {
+                if ((j & 1) && j <= L) den ^= gf.mul_pow(Lam[j], e);
+                e += xe;
+                if (e >= ord) e -= ord;
+            }
+            int val = 0;
+            if (den != 0) {
+                val = gf.mul(num, gf.inv(den));
+                int ex = (pw * (1 - p.fcr)) % ord;
+                if (ex < 0) ex += ord;
+                val = gf.mul_pow(val, ex);
+            }
+            if (val == 0) fail = true; // zero denominator or zero error value: not a valid correction
+            evpos[q2] = i;
+            evval[q2] = val;
+        }
+    }
+
+    // ---- write back
+    int agree = 0;
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) {
+        if (i < n) {
+            int out = r[i];
+            if (!fail) {
+#pragma unroll
+                for (int q2 = 0; q2 < TMAX; ++q2)
+                    if (evpos[q2] == i) out ^= evval[q2];
+            }
+            if (cw) cw[w * n + i] = (uint8_t)out;
+            if (i < k) {
+                msg[w * k + i] = (uint8_t)out;
+                agree += p.m - __popc((unsigned)(out ^ s_key[i]) & (unsigned)(p.q - 1));
+            }
+        }
+    }
+    nerr[w] = (int8_t)(fail ? -1 : L);
+    if (with_key) {
+        key.matches[w] = agree;
+        if (key.detected) key.detected[w] = (uint8_t)(agree >= key.tau);
+    }
+}
+
 // Agreement of stored messages with the key: one word per lane, V bytes of it per load.
 template <typename V>
 __global__ __launch_bounds__(256) void verify_kernel(const uint8_t *__restrict__ msg, int64_t N, int k, int m,
@@ -280,6 +472,20 @@ template <int TMAX>
 hipError_t launch_t(const RsParams &p, const uint8_t *sym, int64_t N, uint8_t *msg, uint8_t *cw, int8_t *nerr,
                     const KeyArgs &key, hipStream_t s)
 {
+    if constexpr (TMAX <= 2) if (p.n <= 16) { // short codes: one word per lane
+        const int64_t blocks = (N + 255) / 256;
+        const int64_t kMaxGrid = 1LL << 30;
+        for (int64_t b0 = 0; b0 < blocks; b0 += kMaxGrid) {
+            const int64_t cnt = blocks - b0 < kMaxGrid ? blocks - b0 : kMaxGrid;
+            const int64_t w0 = b0 * 256;
+            KeyArgs k2 = key;
+            if (k2.matches) k2.matches += w0;
+            if (k2.detected) k2.detected += w0;
+            hipLaunchKernelGGL(rs_decode_lane_kernel<TMAX>, dim3((unsigned)cnt), dim3(256), 0, s, p, sym + w0 * p.n,
+                               N - w0, msg + w0 * p.k, cw ? cw + w0 * p.n : nullptr, nerr + w0, k2);
+        }
+        return hipGetLastError();
+    }
     if (p.n <= 16) return launch_one<16, TMAX, 1>(p, sym, N, msg, cw, nerr, key, s);
     if (p.n <= 64) return launch_one<64, TMAX, 1>(p, sym, N, msg, cw, nerr, key, s);
     if (p.n <= 128) return launch_one<64, TMAX, 2>(p, sym, N, msg, cw, nerr, key, s);
