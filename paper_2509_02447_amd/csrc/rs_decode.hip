@@ -5,8 +5,8 @@
 // or a failure flag.  The paper's decoder is Berlekamp-Welch on the CPU; this kernel reaches the same
 // result through syndromes -> Berlekamp-Massey -> Chien search -> Forney.
 //
-// Mapping (group kernel; short codes use the lane-per-word kernel further down): a group of G lanes owns one codeword (G = 16 for n <= 16, so a 64-wide wavefront decodes
-// four words; G = 64 otherwise, each lane then holds ceil(n/64) symbols).  Lane i of the group holds
+// Mapping of the group kernel (short codes with t <= 2 use the lane-per-word kernel further down): a group of
+// G lanes owns one codeword (G = 16 for n <= 16, so a 64-wide wavefront decodes four words; G = 64 otherwise, each lane then holds ceil(n/64) symbols).  Lane i of the group holds
 // symbol i, i.e. the coefficient of x^(n-1-i).  Syndromes are XOR-reduced across the group (packed
 // four per 32-bit word), the short serial Berlekamp-Massey recursion is replicated in every lane, and
 // Chien search and Forney run one position per lane.  Log / antilog tables live in LDS.  No lane ever

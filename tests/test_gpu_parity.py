@@ -49,6 +49,12 @@ RS_CASES = [
     ("rs(100,84) gf256 t8", dict(m=8, prim_poly=0x11D, n=100, k=84, fcr=1), 8, 300),
     ("rs(255,239) gf256 t8", dict(m=8, prim_poly=0x11D, n=255, k=239, fcr=1), 9, 200),
     ("rs(7,3) gf8", dict(m=3, prim_poly=0xB, n=7, k=3, fcr=1), 10, 640),
+    # short codes with t > 2 stay on the kernel with 16 lanes per word; t <= 2 take the one-word-per-lane kernel
+    ("rs(15,7) gf16 t4", dict(m=4, prim_poly=0x13, n=15, k=7, fcr=1), 11, 900),
+    ("rs(15,9) gf16 t3", dict(m=4, prim_poly=0x13, n=15, k=9, fcr=0), 12, 333),
+    ("rs(15,13) gf16 t1", dict(m=4, prim_poly=0x13, n=15, k=13, fcr=1), 13, 1000),
+    ("rs(9,7) gf256 t1 fcr0", dict(m=8, prim_poly=0x11D, n=9, k=7, fcr=0), 14, 257),
+    ("rs(3,1) gf4 t1", dict(m=2, prim_poly=0x7, n=3, k=1, fcr=1), 15, 130),
 ]
 
 
