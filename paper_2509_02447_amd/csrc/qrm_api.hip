@@ -252,12 +252,13 @@ void residual_sums(const float *w, const float *scale, const std::vector<uint16_
 
 int default_micro_batch(const qrm_ctx *c, int h, int w)
 {
+    // Half a GiB of activations per buffer: measured best for the fused pairs (1024 images at 64 x 64: four per
+    // compute unit, which the workgroups walk through without draining) and for the single-block kernel on wide
+    // tiles (256 images at 128 x 128, 64 at 256 x 256: ~16 k strips per launch).  Cache residency of the two
+    // buffers (128 MiB each) measured worse in both cases.
+    (void)w;
     const size_t per_img = (size_t)h * w * c->C * 2;
-    // One block per launch lives on its two activation buffers staying in the Infinity Cache (128 MiB each).
-    // The fused pairs move half as many bytes per FLOP and their workgroups walk through their images without
-    // draining in between, so they do better with four images per compute unit than with cache residency.
-    const bool fused = c->pairable && w <= kTileW && c->n_blocks >= 2 && !getenv("QRM_DISABLE_PAIRS");
-    size_t mb = ((size_t)(fused ? 512 : 128) << 20) / (per_img ? per_img : 1);
+    size_t mb = ((size_t)512 << 20) / (per_img ? per_img : 1);
     if (mb < 64) mb = 64;
     if (mb > 8192) mb = 8192;
     return (int)mb;
