@@ -296,9 +296,14 @@ __device__ __forceinline__ void lds_accumulate(float *slot16, const float (&tv)[
 // order, so the sums are formed in program order as before.
 __device__ __forceinline__ void lds_accumulate4(float *slot4, const float (&tv)[4], bool pred)
 {
+    // (written as assembly: the compiler, not knowing which bytes the direct-to-LDS loads in flight fill, would
+    // otherwise wait for all of them in front of every one of these updates)
     if (pred) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) (void)atomicAdd(slot4 + e, tv[e]); // ds_add_f32: the result is not asked for
+        const lrow_t a = lds_address(slot4);
+        asm volatile("ds_add_f32 %0, %1\n\tds_add_f32 %0, %2 offset:4\n\tds_add_f32 %0, %3 offset:8\n\tds_add_f32 %0, %4 offset:12"
+                     :
+                     : "v"(a), "v"(tv[0]), "v"(tv[1]), "v"(tv[2]), "v"(tv[3])
+                     : "memory");
     }
 }
 
