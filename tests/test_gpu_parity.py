@@ -760,6 +760,46 @@ def test_verification_error_statuses(qrm):
     ctx.close()
 
 
+def test_whole_chain_raw_image_to_verdict(qrm):
+    """Every stage in a row, device pointers handed from one call to the next: raw interleaved 384 x 512 images ->
+    resize + centre crop (256 x 256) -> variance-based choice of the tile -> crop, extractor, threshold, Reed-Solomon,
+    comparison with a key; against the same chain of oracles."""
+    cfg = synth.CONFIGS["C2"]
+    wts = synth.config_weights(cfg)
+    N, Hin, Win = 10, 384, 512
+    rng = np.random.default_rng(77)
+    raw = (rng.integers(0, 256, size=(N, Hin, Win, 3)) // 3 + 60).astype(np.uint8)
+    for i in range(N):                                # one busy region per image, so that the selection is clear-cut
+        y, x = int(rng.integers(0, Hin - 140)), int(rng.integers(64, Win - 204))
+        raw[i, y:y + 140, x:x + 140] = rng.integers(0, 256, size=(140, 140, 3), dtype=np.uint8)
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    d_raw = dev(raw)
+    d_img = empty((N, 3, cfg.H, cfg.W), torch.uint8)
+    ctx.qrm_preprocess(d_raw, N, Hin, Win, cfg.H, None, 0, d_img)
+    d_off = empty((N, 2), torch.int32)
+    ctx.qrm_select_tiles_variance(d_img, N, cfg.H, cfg.W, cfg.tile, cfg.tile // 2, d_off)
+    # oracle side of the first two stages, needed for the key
+    img = pre_oracle.preprocess(raw, cfg.H)
+    off, _ = tileselect.select_tiles_variance(img, cfg.tile, cfg.tile // 2, channel_weights(wts["std"]))
+    ref = oracle.detect(wts, img, off, cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    key = ref["msg"][3].copy()
+    tau = qrm.binding.qrm_key_threshold(cfg.k * cfg.m, 1e-6)
+    ctx.qrm_set_key(key, tau)
+    d_logits, d_bits = empty((N, cfg.n_bits), torch.float32), empty((N, cfg.n_bits), torch.uint8)
+    d_msg, d_cw, d_ne = empty((N, cfg.k), torch.uint8), empty((N, cfg.n), torch.uint8), empty((N,), torch.int8)
+    d_matches, d_det = empty((N,), torch.int32), empty((N,), torch.uint8)
+    ctx.qrm_detect_verify(d_img, N, cfg.H, cfg.W, d_off, cfg.tile, d_logits, d_bits, d_msg, d_cw, d_ne, d_matches, d_det)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_img.cpu().numpy(), img)
+    assert np.array_equal(d_off.cpu().numpy(), off)
+    got = dict(logits=d_logits.cpu().numpy(), bits=d_bits.cpu().numpy(), msg=d_msg.cpu().numpy(),
+               codeword=d_cw.cpu().numpy(), nerr=d_ne.cpu().numpy())
+    check_detect(cfg, wts, img, off, got, "raw image -> verdict")
+    rm, rd = keycheck.verify_key(got["msg"], key, cfg.m, keycheck.key_threshold(cfg.k * cfg.m, Fraction(1e-6)))
+    assert np.array_equal(d_matches.cpu().numpy(), rm) and np.array_equal(d_det.cpu().numpy(), rd)
+    ctx.close()
+
+
 def test_matrix_rate_probe_reports_plausible_rates(qrm):
     """The diagnostic probe: zeros run near the published rate, random operands slower, both far above zero."""
     ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
