@@ -112,8 +112,9 @@ QRM_API void qrm_destroy(qrm_ctx *ctx);
 QRM_API const char *qrm_last_error(const qrm_ctx *ctx);
 
 /*
- * Images per internal micro-batch of the extractor (activations of one micro-batch ping-pong
- * between two workspace buffers so that they stay cache-resident).  0 restores the default.
+ * Images per internal micro-batch of the extractor (the activations of one micro-batch ping-pong
+ * between two workspace buffers).  0 restores the default: half a GiB of activations per buffer,
+ * e.g. 1024 images for 64 x 64 tiles and 64 channels.
  */
 QRM_API qrm_status qrm_set_micro_batch(qrm_ctx *ctx, int32_t images);
 
