@@ -222,7 +222,7 @@ __device__ __forceinline__ void source_taps(int dst, int n_in, int n_res, int &i
     w1 = (a * (1 << kCoefBits) + n_res) / den; // round(fraction * 2048)
 }
 
-template <int VEC>
+template <int VEC, bool WORDS>
 __global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restrict__ raw, PreArgs a,
                                                          const int32_t *__restrict__ off, uint8_t *__restrict__ out)
 {
@@ -238,9 +238,12 @@ __global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restri
     for (int t = tid; t < a.T; t += 256) {
         int i0, i1, w1;
         source_taps(a.cx + ox + t, a.W_in, a.Wr, i0, i1, w1);
-        s_x0[t] = i0 * 3; // byte offsets within a raw row
-        s_x1[t] = i1 * 3;
-        s_w1[t] = (uint16_t)w1;
+        // A pixel's three bytes are fetched with ONE (unaligned) dword load: bytes 3i-1 .. 3i+2 for i > 0 (the colours
+        // are its upper three bytes), bytes 0 .. 3 for i = 0; both stay inside the row (rows have at least two pixels
+        // on this path).  Offset and "skip one byte" flag per tap; the flags ride in the weight's spare bits.
+        s_x0[t] = WORDS ? (i0 > 0 ? 3 * i0 - 1 : 0) : i0 * 3;
+        s_x1[t] = WORDS ? (i1 > 0 ? 3 * i1 - 1 : 0) : i1 * 3;
+        s_w1[t] = (uint16_t)(w1 | (i0 > 0 ? 0x4000 : 0) | (i1 > 0 ? 0x8000 : 0));
     }
     __syncthreads();
     const uint8_t *img = raw + n * (int64_t)a.H_in * a.W_in * 3;
@@ -258,11 +261,26 @@ __global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restri
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             const int b0 = s_x0[tx + v], b1 = s_x1[tx + v];
-            const int wx1 = s_w1[tx + v], wx0 = (1 << kCoefBits) - wx1;
+            const int wf = s_w1[tx + v];
+            const int wx1 = wf & 0x0fff, wx0 = (1 << kCoefBits) - wx1;
+            uint32_t p00 = 0, p01 = 0, p10 = 0, p11 = 0; // WORDS: the three colours of the four taps, one per byte
+            if (WORDS) {
+                __builtin_memcpy(&p00, row0 + b0, 4);
+                __builtin_memcpy(&p01, row0 + b1, 4);
+                __builtin_memcpy(&p10, row1 + b0, 4);
+                __builtin_memcpy(&p11, row1 + b1, 4);
+                const int s0 = (wf & 0x4000) ? 8 : 0, s1 = (wf & 0x8000) ? 8 : 0;
+                p00 >>= s0; p10 >>= s0;
+                p01 >>= s1; p11 >>= s1;
+            }
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
-                const int top = row0[b0 + c] * wx0 + row0[b1 + c] * wx1; // < 2^19
-                const int bot = row1[b0 + c] * wx0 + row1[b1 + c] * wx1;
+                const int a00 = WORDS ? (int)((p00 >> (8 * c)) & 0xffu) : row0[b0 + c];
+                const int a01 = WORDS ? (int)((p01 >> (8 * c)) & 0xffu) : row0[b1 + c];
+                const int a10 = WORDS ? (int)((p10 >> (8 * c)) & 0xffu) : row1[b0 + c];
+                const int a11 = WORDS ? (int)((p11 >> (8 * c)) & 0xffu) : row1[b1 + c];
+                const int top = a00 * wx0 + a01 * wx1; // < 2^19
+                const int bot = a10 * wx0 + a11 * wx1;
                 const uint32_t s = (uint32_t)(top * wy0 + bot * wy1);    // <= 255 * 2^22 < 2^30
                 const uint32_t val = (s + (1u << (2 * kCoefBits - 1))) >> (2 * kCoefBits);
                 pk[c] |= val << (8 * v);
@@ -322,8 +340,11 @@ hipError_t launch_preprocess(const uint8_t *raw, int64_t N, int H_in, int W_in, 
         const int32_t *off0 = off ? off + 2 * n0 : nullptr;
         uint8_t *out0 = out + n0 * 3 * (int64_t)T * T;
         const dim3 grid((unsigned)cnt, (unsigned)strips);
-        if (vec) hipLaunchKernelGGL(preprocess_kernel<4>, grid, dim3(256), 0, s, raw0, a, off0, out0);
-        else hipLaunchKernelGGL(preprocess_kernel<1>, grid, dim3(256), 0, s, raw0, a, off0, out0);
+        const bool words = W_in >= 2; // a one-pixel row has no room for a dword
+        if (vec && words) hipLaunchKernelGGL((preprocess_kernel<4, true>), grid, dim3(256), 0, s, raw0, a, off0, out0);
+        else if (vec) hipLaunchKernelGGL((preprocess_kernel<4, false>), grid, dim3(256), 0, s, raw0, a, off0, out0);
+        else if (words) hipLaunchKernelGGL((preprocess_kernel<1, true>), grid, dim3(256), 0, s, raw0, a, off0, out0);
+        else hipLaunchKernelGGL((preprocess_kernel<1, false>), grid, dim3(256), 0, s, raw0, a, off0, out0);
     }
     return hipGetLastError();
 }
