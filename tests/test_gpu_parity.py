@@ -465,6 +465,9 @@ PRE_CASES = [  # N, H_in, W_in, size, tile (0 = whole image)
     (2, 40, 56, 90, 32),        # enlarging
     (4, 333, 500, 96, 31),      # tile width not a multiple of 4: byte stores
     (2, 1024, 768, 256, 128),
+    (2, 7, 1, 3, 0),            # one-pixel rows: no room for word loads
+    (2, 1, 9, 4, 0),            # a single row
+    (3, 2, 2, 8, 4),            # 2 x 2 image enlarged
 ]
 
 
