@@ -222,12 +222,51 @@ __device__ __forceinline__ void source_taps(int dst, int n_in, int n_res, int &i
     w1 = (a * (1 << kCoefBits) + n_res) / den; // round(fraction * 2048)
 }
 
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// One colour of one window pixel from the dwords that hold its four taps (p00 p01 above p10 p11).  sel picks the
+// colour's byte out of the left tap (low half) and the right tap (high half), wx = wx0 | wx1 << 16.  The horizontal
+// pass is a two-term dot product of 16-bit fields (< 2^19), the vertical pass two 24-bit products (< 2^30): all
+// full-rate instructions, and the same integers as the plain formula.
+__device__ __forceinline__ uint32_t bilinear_byte(uint32_t p00, uint32_t p01, uint32_t p10, uint32_t p11, uint32_t sel,
+                                                  uint32_t wx, uint32_t wy0, uint32_t wy1)
+{
+    const uint32_t t = __builtin_amdgcn_perm(p01, p00, sel), b = __builtin_amdgcn_perm(p11, p10, sel);
+    const uint32_t top = __builtin_amdgcn_udot2(__builtin_bit_cast(ushort2_t, t), __builtin_bit_cast(ushort2_t, wx), 0u, false);
+    const uint32_t bot = __builtin_amdgcn_udot2(__builtin_bit_cast(ushort2_t, b), __builtin_bit_cast(ushort2_t, wx), 0u, false);
+    const uint32_t sum = __umul24(top, wy0) + (__umul24(bot, wy1) + (1u << (2 * kCoefBits - 1)));
+    return sum >> (2 * kCoefBits);
+}
+constexpr uint32_t kSelect = 0x0c040c00u; // byte 0 of the second operand -> bits 0..7, byte 0 of the first -> 16..23
+
+// Walks the (row, pixel group) pairs of a strip, 256 at a time, without a division per step.
+struct StripWalk {
+    int row, grp, d_row, d_grp, groups;
+    __device__ StripWalk(int tid, int groups_) : groups(groups_)
+    {
+        row = tid / groups;
+        grp = tid - row * groups;
+        d_row = 256 / groups;
+        d_grp = 256 - d_row * groups;
+    }
+    __device__ void next()
+    {
+        row += d_row;
+        grp += d_grp;
+        if (grp >= groups) {
+            grp -= groups;
+            ++row;
+        }
+    }
+};
+
 template <int VEC, bool WORDS>
 __global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restrict__ raw, PreArgs a,
                                                          const int32_t *__restrict__ off, uint8_t *__restrict__ out)
 {
-    __shared__ int s_x0[kMaxTile], s_x1[kMaxTile];
-    __shared__ uint16_t s_w1[kMaxTile];
+    __shared__ int s_x0[kMaxTile], s_x1[kMaxTile], s_y0[kMaxTile], s_y1[kMaxTile];
+    __shared__ uint32_t s_wx[kMaxTile], s_sel[kMaxTile];
+    __shared__ uint16_t s_wy[kMaxTile];
     const int tid = threadIdx.x;
     const int64_t n = blockIdx.x;
     int oy = 0, ox = 0;
@@ -235,56 +274,53 @@ __global__ __launch_bounds__(256) void preprocess_kernel(const uint8_t *__restri
         oy = clampi(off[2 * n], 0, a.x - a.T);
         ox = clampi(off[2 * n + 1], 0, a.x - a.T);
     }
+    const int r_begin = blockIdx.y * a.rows_per_block, r_end = min(a.T, r_begin + a.rows_per_block);
     for (int t = tid; t < a.T; t += 256) {
         int i0, i1, w1;
         source_taps(a.cx + ox + t, a.W_in, a.Wr, i0, i1, w1);
         // A pixel's three bytes are fetched with ONE (unaligned) dword load: bytes 3i-1 .. 3i+2 for i > 0 (the colours
         // are its upper three bytes), bytes 0 .. 3 for i = 0; both stay inside the row (rows have at least two pixels
-        // on this path).  Offset and "skip one byte" flag per tap; the flags ride in the weight's spare bits.
+        // on this path; one-pixel rows are read byte by byte).  The byte selector carries the "skip one".
         s_x0[t] = WORDS ? (i0 > 0 ? 3 * i0 - 1 : 0) : i0 * 3;
         s_x1[t] = WORDS ? (i1 > 0 ? 3 * i1 - 1 : 0) : i1 * 3;
-        s_w1[t] = (uint16_t)(w1 | (i0 > 0 ? 0x4000 : 0) | (i1 > 0 ? 0x8000 : 0));
+        s_sel[t] = kSelect + (WORDS && i0 > 0 ? 1u : 0u) + (WORDS && i1 > 0 ? 0x10000u : 0u);
+        s_wx[t] = (uint32_t)((1 << kCoefBits) - w1) | (uint32_t)w1 << 16;
+    }
+    for (int t = tid; t < r_end - r_begin; t += 256) {
+        int y0, y1, wy1;
+        source_taps(a.cy + oy + r_begin + t, a.H_in, a.Hr, y0, y1, wy1);
+        s_y0[t] = y0;
+        s_y1[t] = y1;
+        s_wy[t] = (uint16_t)wy1;
     }
     __syncthreads();
     const uint8_t *img = raw + n * (int64_t)a.H_in * a.W_in * 3;
     uint8_t *dst = out + n * 3 * (int64_t)a.T * a.T;
-    const int r_begin = blockIdx.y * a.rows_per_block, r_end = min(a.T, r_begin + a.rows_per_block);
-    const int groups = a.T / VEC; // pixel groups per row
     const int64_t plane = (int64_t)a.T * a.T;
-    for (int idx = tid; idx < (r_end - r_begin) * groups; idx += 256) {
-        const int ty = r_begin + idx / groups, tx = (idx % groups) * VEC;
-        int y0, y1, wy1;
-        source_taps(a.cy + oy + ty, a.H_in, a.Hr, y0, y1, wy1);
-        const int wy0 = (1 << kCoefBits) - wy1;
-        const uint8_t *row0 = img + (int64_t)y0 * a.W_in * 3, *row1 = img + (int64_t)y1 * a.W_in * 3;
+    for (StripWalk w(tid, a.T / VEC); w.row < r_end - r_begin; w.next()) {
+        const int ty = r_begin + w.row, tx = w.grp * VEC;
+        const uint32_t wy1 = s_wy[w.row], wy0 = (1u << kCoefBits) - wy1;
+        const uint8_t *row0 = img + (int64_t)s_y0[w.row] * a.W_in * 3, *row1 = img + (int64_t)s_y1[w.row] * a.W_in * 3;
         uint32_t pk[3] = {0u, 0u, 0u};
 #pragma unroll
         for (int v = 0; v < VEC; ++v) {
             const int b0 = s_x0[tx + v], b1 = s_x1[tx + v];
-            const int wf = s_w1[tx + v];
-            const int wx1 = wf & 0x0fff, wx0 = (1 << kCoefBits) - wx1;
-            uint32_t p00 = 0, p01 = 0, p10 = 0, p11 = 0; // WORDS: the three colours of the four taps, one per byte
+            const uint32_t wx = s_wx[tx + v], sel = s_sel[tx + v];
+            uint32_t p00, p01, p10, p11; // the three colours of the four taps, one per byte
             if (WORDS) {
                 __builtin_memcpy(&p00, row0 + b0, 4);
                 __builtin_memcpy(&p01, row0 + b1, 4);
                 __builtin_memcpy(&p10, row1 + b0, 4);
                 __builtin_memcpy(&p11, row1 + b1, 4);
-                const int s0 = (wf & 0x4000) ? 8 : 0, s1 = (wf & 0x8000) ? 8 : 0;
-                p00 >>= s0; p10 >>= s0;
-                p01 >>= s1; p11 >>= s1;
+            } else {
+                p00 = row0[b0] | row0[b0 + 1] << 8 | row0[b0 + 2] << 16;
+                p01 = row0[b1] | row0[b1 + 1] << 8 | row0[b1 + 2] << 16;
+                p10 = row1[b0] | row1[b0 + 1] << 8 | row1[b0 + 2] << 16;
+                p11 = row1[b1] | row1[b1 + 1] << 8 | row1[b1 + 2] << 16;
             }
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                const int a00 = WORDS ? (int)((p00 >> (8 * c)) & 0xffu) : row0[b0 + c];
-                const int a01 = WORDS ? (int)((p01 >> (8 * c)) & 0xffu) : row0[b1 + c];
-                const int a10 = WORDS ? (int)((p10 >> (8 * c)) & 0xffu) : row1[b0 + c];
-                const int a11 = WORDS ? (int)((p11 >> (8 * c)) & 0xffu) : row1[b1 + c];
-                const int top = a00 * wx0 + a01 * wx1; // < 2^19
-                const int bot = a10 * wx0 + a11 * wx1;
-                const uint32_t s = (uint32_t)(top * wy0 + bot * wy1);    // <= 255 * 2^22 < 2^30
-                const uint32_t val = (s + (1u << (2 * kCoefBits - 1))) >> (2 * kCoefBits);
-                pk[c] |= val << (8 * v);
-            }
+            for (int c = 0; c < 3; ++c)
+                pk[c] |= bilinear_byte(p00, p01, p10, p11, sel + c * 0x10001u, wx, wy0, wy1) << (8 * v);
         }
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
@@ -328,12 +364,12 @@ hipError_t launch_preprocess(const uint8_t *raw, int64_t N, int H_in, int W_in, 
     preprocess_resized_shape(H_in, W_in, x, &a.Hr, &a.Wr);
     a.cy = (a.Hr - x) / 2;
     a.cx = (a.Wr - x) / 2;
+    const bool vec = T % 4 == 0 && ((uintptr_t)out & 3u) == 0;
+    const int64_t kMaxGrid = 1LL << 30;
     // enough workgroups for the chip when there are few images, few column-tap computations otherwise
     int strips = (int)std::min<int64_t>((T + 7) / 8, std::max<int64_t>(1, 2048 / N));
     a.rows_per_block = (T + strips - 1) / strips;
     strips = (T + a.rows_per_block - 1) / a.rows_per_block;
-    const bool vec = T % 4 == 0 && ((uintptr_t)out & 3u) == 0;
-    const int64_t kMaxGrid = 1LL << 30;
     for (int64_t n0 = 0; n0 < N; n0 += kMaxGrid) {
         const int64_t cnt = N - n0 < kMaxGrid ? N - n0 : kMaxGrid;
         const uint8_t *raw0 = raw + n0 * (int64_t)H_in * W_in * 3;

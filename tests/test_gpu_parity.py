@@ -468,6 +468,10 @@ PRE_CASES = [  # N, H_in, W_in, size, tile (0 = whole image)
     (2, 7, 1, 3, 0),            # one-pixel rows: no room for word loads
     (2, 1, 9, 4, 0),            # a single row
     (3, 2, 2, 8, 4),            # 2 x 2 image enlarged
+    (1, 1200, 1100, 1024, 0),   # the widest window the kernel takes
+    (2, 640, 250, 100, 48),     # scale 2.5; rows of 750 bytes
+    (2, 653, 251, 100, 48),     # a scale that is no simple fraction; rows of 753 bytes
+    (2, 96, 131, 64, 0),        # rows of 393 bytes: every alignment of a row's first byte
 ]
 
 
@@ -490,6 +494,25 @@ def test_preprocess_bit_exact(qrm, N, H_in, W_in, size, tile):
         ctx.qrm_preprocess(dev(raw), N, H_in, W_in, size, None, tile, d_out)
         torch.cuda.synchronize()
         assert np.array_equal(d_out.cpu().numpy(), pre_oracle.preprocess(raw, size, np.zeros((N, 2), np.int32), tile))
+    ctx.close()
+
+
+@pytest.mark.parametrize("shift_in,shift_out", [(5, 0), (0, 3), (13, 1)])
+def test_preprocess_buffers_at_odd_addresses(qrm, shift_in, shift_out):
+    """Raw and output buffers that start at any byte: word loads and dword stores must not assume more."""
+    N, H_in, W_in, size = 2, 131, 157, 64
+    rng = np.random.default_rng(shift_in * 16 + shift_out)
+    raw = rng.integers(0, 256, size=(N, H_in, W_in, 3), dtype=np.uint8)
+    ref = pre_oracle.preprocess(raw, size, None, 0)
+    ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
+    buf_in = torch.zeros(raw.size + 16, dtype=torch.uint8, device="cuda")
+    buf_in[shift_in:shift_in + raw.size] = dev(raw.reshape(-1))
+    buf_out = torch.full((ref.size + 16,), 0xEE, dtype=torch.uint8, device="cuda")
+    ctx.qrm_preprocess(buf_in[shift_in:], N, H_in, W_in, size, None, 0, buf_out[shift_out:])
+    torch.cuda.synchronize()
+    got = buf_out.cpu().numpy()
+    assert np.array_equal(got[shift_out:shift_out + ref.size], ref.reshape(-1))
+    assert (got[:shift_out] == 0xEE).all() and (got[shift_out + ref.size:] == 0xEE).all()   # nothing written outside
     ctx.close()
 
 
