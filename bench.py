@@ -188,7 +188,11 @@ def main() -> int:
                                                   stream=stream))
     pre_full_bytes = n_raw * (4 * 3 * cfg.H * cfg.W + 3 * cfg.H * cfg.W)
     pre_tile_bytes = n_raw * (4 * 3 * l2 + 3 * l2 + 8)
-    del raw, pre_full, pre_tile
+    # a yardstick for the stages above: the same box's plain device copy of the raw images' volume (read + write)
+    cp_dst = torch.empty_like(raw)
+    t_copy = timed(lambda: cp_dst.copy_(raw))
+    copy_bytes = 2 * raw.numel()
+    del raw, pre_full, pre_tile, cp_dst
     # what the matrix pipes sustain with nothing else running, by operand data (the clock follows the power budget)
     matrix_probe = {"zeros_tflops": round(ctx.qrm_matrix_rate_probe(0), 1),
                     "random_data_tflops": round(ctx.qrm_matrix_rate_probe(2), 1),
@@ -198,6 +202,9 @@ def main() -> int:
                                                  "frac_of_it": round(roofline["achieved"] / matrix_probe["random_data_tflops"], 4)}
     stages = {
         "matrix_pipe_probe": matrix_probe,
+        "device_copy": {"us": round(t_copy * 1e6, 2), "GBs_read_plus_write": round(copy_bytes / t_copy / 1e9, 1),
+                        "frac_hbm": round(copy_bytes / t_copy / 1e9 / PEAK_HBM_GBS, 4),
+                        "note": "torch copy_ of the raw-image buffer: what a plain read + write stream reaches here"},
         "preprocess_whole_image": {"us": round(t_pre_full * 1e6, 2), "images_per_s": round(n_raw / t_pre_full, 0),
                                    "algorithmic_GBs": round(pre_full_bytes / t_pre_full / 1e9, 1),
                                    "frac_hbm": round(pre_full_bytes / t_pre_full / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},

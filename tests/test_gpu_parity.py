@@ -3,6 +3,7 @@
 Bit-exact for tile crops, symbols and Reed-Solomon outputs; extractor logits within
 2e-2 * max(1, |ref|) and hard bits equal wherever |oracle logit| > 1e-2.
 """
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -379,6 +380,33 @@ def test_detect_equals_separate_calls(qrm):
     gm, gc, ge = gpu_rs_decode(ctx, syms)
     assert np.array_equal(gm, got["msg"]) and np.array_equal(gc, got["codeword"]) and np.array_equal(ge, got["nerr"])
     ctx.close()
+
+
+def test_poisoned_workspace_gives_the_same_results(qrm, tmp_path):
+    """No kernel reads workspace bytes that no kernel wrote: a child process with every new workspace filled with
+    0xFF bytes (NaN as bf16 and as fp32) computes what this process computes."""
+    import subprocess
+    import sys
+    import poison_cases
+    mine = poison_cases.run_cases()
+    path = str(tmp_path / "poisoned.npz")
+    env = dict(os.environ, QRM_POISON_WORKSPACE="1")
+    r = subprocess.run([sys.executable, os.path.join(os.path.dirname(__file__), "poison_cases.py"), path], env=env,
+                       capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    theirs = np.load(path)
+    assert sorted(theirs.files) == sorted(mine)
+    for key, a in mine.items():
+        b = theirs[key]
+        assert np.isfinite(b).all(), key
+        if key.endswith("logits"):   # sums over LDS atomics: the order of the additions is not fixed
+            twin = mine[key.replace("_0_logits", "_1_logits").replace("_1_logits", "_0_logits") if "_0_" in key
+                        else key.replace("_1_logits", "_0_logits")]
+            print(f"[poison] {key}: max |poisoned - plain| {float(np.abs(a - b).max()):.2e}, "
+                  f"between two plain calls {float(np.abs(a - twin).max()):.2e}")
+            assert (np.abs(a - b) <= 5e-4 * np.maximum(1.0, np.abs(a))).all(), (key, float(np.abs(a - b).max()))
+        else:
+            assert np.array_equal(a, b), key
 
 
 def test_detect_on_two_streams(qrm):
