@@ -1,9 +1,9 @@
 """Detection on a few small batches of every configuration shape; run as a script it writes the logits to a file.
 
-Used by the GPU test that runs this file in a child process with QRM_POISON_WORKSPACE=1 (the library then fills
-every new workspace with 0xFF bytes, NaN as bf16 and as fp32) and compares with the same calls in the parent,
-where workspaces start as whatever the allocator hands out: a kernel that reads workspace bytes which no kernel
-wrote would show up as a difference (or as NaN).
+Used by the GPU test that runs this file in a child process under one of the library's environment switches -
+QRM_POISON_WORKSPACE=1 (every new workspace is filled with 0xFF bytes, NaN as bf16 and as fp32: a kernel that
+reads workspace bytes which no kernel wrote would show up as a difference, or as NaN) or QRM_DISABLE_PAIRS=1 (one
+launch per block) - and compares with the same calls in the parent.
 """
 import os
 import sys
