@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
 # copy kernel of known size (profiles/conv_pair_c2_hbm_traffic.txt), for the fused pair of C -> C blocks at the
 # default micro-batch of 1024 images: 514.41 MiB read + 512.57 MiB written; algorithmic 2 x 512 MiB.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1076878405
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1076853382
 
 
 def main() -> int:
