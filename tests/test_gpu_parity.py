@@ -94,6 +94,38 @@ def test_rs_decode_small_batches(qrm, N):
     ctx.close()
 
 
+def _random_codes(count, seed):
+    """Seeded random code parameters over every supported field: (m, prim_poly, n, k, fcr)."""
+    prim = {2: 0x7, 3: 0xB, 4: 0x13, 5: 0x25, 6: 0x43, 7: 0x89, 8: 0x11D}
+    rng = np.random.default_rng(seed)
+    codes = []
+    while len(codes) < count:
+        m = int(rng.integers(2, 9))
+        n = int(rng.integers(3, (1 << m)))
+        t = int(rng.integers(1, min(8, (n - 1) // 2) + 1))
+        codes.append(dict(m=m, prim_poly=prim[m], n=n, k=n - 2 * t, fcr=int(rng.choice([0, 1, 1, 2, 5, (1 << m) - 2]))))
+    return codes
+
+
+def test_rs_decode_random_code_parameters(qrm):
+    """Thirty random codes over GF(4) .. GF(256), full length and shortened, t = 1..8, several first roots: words with
+    0 .. t+1 injected errors and plain random words, bit-exact against the oracle (which kernel a code takes - one
+    word per lane, 16 or 64 lanes per word - follows from n and t)."""
+    for i, code in enumerate(_random_codes(30, 20250902)):
+        t = (code["n"] - code["k"]) // 2
+        msgs, err, ninj = synth.rs_cases(20 + i, 300, code["n"], code["k"], code["m"], max_err=t + 1)
+        clean = oracle.rs_encode(msgs, **code)
+        allw = np.concatenate([clean ^ err, synth.random_words(20 + i, 100, code["n"], code["m"])], axis=0)
+        ctx = qrm.Context(rs=code)
+        gm, gc, ge = gpu_rs_decode(ctx, allw)
+        om, oc, oe = oracle.rs_decode(allw, **code)
+        assert np.array_equal(ge, oe), f"{code}: nerr differs at {np.nonzero(ge != oe)[0][:10]}"
+        assert np.array_equal(gm, om) and np.array_equal(gc, oc), f"{code}"
+        ok = ninj <= t
+        assert np.array_equal(ge[:300][ok], ninj[ok]) and np.array_equal(gm[:300][ok], msgs[ok]), f"{code}"
+        ctx.close()
+
+
 def test_rs_decode_full_size_sets(qrm):
     """The two stand-alone codeword sets at their full sizes: 1024 x RS(15,11)/GF(16) and
     2^20 x RS(12,8)/GF(256), 0..3 random symbol errors."""
