@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the batched watermark-detection path on one MI355X.
 
-One step = one pass of the whole hot path (tile crop + normalise fused into the first convolution,
-the convolutional extractor, thresholding, symbol packing, Reed-Solomon decoding) over the 4096-image
-"tiled detection" configuration, with images, origins and weights already resident in device memory.
+One step = one pass of the whole hot path (tile crop + normalise fused into the first convolution, the
+convolutional extractor, thresholding, symbol packing, Reed-Solomon decoding) over one configuration's batch,
+with images, origins and weights already resident in device memory.
 
-Prints ONE JSON line: images/s (whole job), the roofline of the dominant kernel (the fused pair of
-C -> C 3x3 convolution blocks on the bf16 matrix cores; duration per launch measured with HIP events on
-the launch stream), per-stage figures for the tile-crop and Reed-Solomon kernels, and the CPU oracle timed on
-this machine's host cores on a bounded sample of the same workload.
+The headline (`value`, `config`, `roofline`) is the largest device-resident configuration, C4 at its full
+16 384 images.  `stages.configs` carries the other full-size configurations timed in the same run: C2, C3, and
+C5 streamed from pinned host memory at its full 128 chunks x 8192 images (with the bare upload rate of the same
+chunks measured beside it).  Every configuration reports images/s, the executed matrix FLOPs as a fraction of the
+bf16 peak, and the duration of every kind of kernel launch measured with HIP events on the launch stream.
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -25,10 +28,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a
-# copy kernel of known size (profiles/conv_pair_c2_hbm_traffic.txt), for the fused pair of C -> C blocks at the
-# default micro-batch of 1024 images: 514.41 MiB read + 512.57 MiB written; algorithmic 2 x 512 MiB.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 1076853382
+# HBM bytes per launch of a configuration's dominant kernel.  These are RECORDED figures, not measured by this
+# script: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command, scaled by a copy kernel of known
+# size (the summaries under profiles/ give the commands), at the commit named.  A record applies only while the
+# kernel, the micro-batch and the image count it was taken on are unchanged; otherwise the line reports null.
+RECORDED_TRAFFIC = {
+    # (configuration, launch kind): bytes per launch, where it was measured
+    ("C2", "pair_mid"): {"bytes": 1076853382, "commit": "dae85d0", "images_per_launch": 1024,
+                         "source": "profiles/conv_pair_c2_hbm_traffic.txt"},
+}
+
+HOST_THREADS = min(16, os.cpu_count() or 1)
+
+
+def log(msg: str) -> None:
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
 def main() -> int:
@@ -36,14 +50,18 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="C2", help="C2 (headline), C3 or C4")
+    ap.add_argument("--config", default="all",
+                    help="all (default): headline C4 plus C2, C3 and streamed C5 under stages.configs; "
+                         "C2 / C3 / C4 / C5: that configuration alone")
     ap.add_argument("--images", type=int, default=0, help="override the number of images (0 = the configuration's)")
     ap.add_argument("--micro-batch", type=int, default=0)
-    ap.add_argument("--cpu-sample", type=int, default=256, help="images the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="images the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--policy", default="random", choices=["random", "random_grid", "fixed"])
-    ap.add_argument("--chunks", type=int, default=16, help="C5 only: chunks per step (a full C5 pass is 128)")
-    ap.add_argument("--chunk-images", type=int, default=8192, help="C5 only: images per pinned host chunk")
-    ap.add_argument("--streams", type=int, default=3, help="C5 only: chunks in flight (staging buffers) of the upload / compute / download pipeline")
+    ap.add_argument("--chunks", type=int, default=128, help="C5: chunks per pass (the full configuration is 128)")
+    ap.add_argument("--chunk-images", type=int, default=8192, help="C5: images per pinned host chunk")
+    ap.add_argument("--streams", type=int, default=3, help="C5: chunks in flight (staging buffers) of the upload / compute / download pipeline")
+    ap.add_argument("--stream-passes", type=int, default=2, help="C5: timed passes over all chunks (after one warm-up pass)")
+    ap.add_argument("--no-stage-kernels", action="store_true", help="skip the stand-alone stage kernels (tile crop, RS decode, ...)")
     ap.add_argument("--calibration-copy", type=int, default=0,
                     help="MiB of a plain device-to-device copy issued once before the timed region: the kernel of "
                          "known size that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -62,23 +80,93 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
-    cfg = synth.CONFIGS[args.config]
+    env = dict(args=args, np=np, torch=torch, synth=synth, q=q)
+
     if args.config == "C5":
-        return bench_stream(args, cfg, torch, np, synth, q)
+        res = bench_stream(env, args.steps, args.warmup)
+        out = headline(res, args)
+        out["stages"] = res["stages"]
+        print(json.dumps(out))
+        return 0
+
+    head_name = "C4" if args.config == "all" else args.config
+    res = bench_resident(env, head_name, args.steps, args.warmup, cpu_sample=args.cpu_sample,
+                         stage_kernels=False)
+    out = headline(res, args)
+    stages = {}
+    if args.config == "all":
+        configs = {}
+        for name in ("C2", "C3"):
+            try:
+                sub = bench_resident(env, name, args.steps, args.warmup, cpu_sample=0,
+                                     stage_kernels=(name == "C2" and not args.no_stage_kernels))
+                if "stage_kernels" in sub:
+                    stages.update(sub.pop("stage_kernels"))
+                configs[name] = summary(sub)
+            except Exception as ex:   # a failing sub-configuration must not take the headline with it
+                configs[name] = {"error": repr(ex)}
+        try:
+            sub = bench_stream(env, args.stream_passes, 1)
+            configs["C5"] = summary(sub)
+        except Exception as ex:
+            configs["C5"] = {"error": repr(ex)}
+        stages["configs"] = configs
+    stages["launch_kinds"] = res["launch_kinds"]
+    stages["extractor_mfma_tflops"] = res["extractor_mfma_tflops"]
+    stages["extractor_frac_of_bf16_peak"] = res["extractor_frac_of_bf16_peak"]
+    stages["extractor_nominal_tflops_incl_final_conv"] = res["extractor_nominal_tflops_incl_final_conv"]
+    out["stages"] = stages
+    print(json.dumps(out))
+    return 0
+
+
+def headline(res: dict, args) -> dict:
+    return {
+        "metric": "images/sec end-to-end detection on 1 MI355X",
+        "value": res["value"], "unit": "images/s", "n_gpus": 1, "steps": res["steps"], "warmup": res["warmup"],
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": res["config"],
+        "roofline": res["roofline"],
+        "cpu_baseline": res.get("cpu_baseline"),
+        "context": "paper: 2.43x over its sequential baseline; Stable Signature ~30 min per 1M 256x256 images "
+                   "(~556 img/s) on 1x H100 + EPYC 9534 (context only, other hardware)",
+    }
+
+
+def summary(res: dict) -> dict:
+    """A sub-configuration's entry under stages.configs."""
+    keep = ("value", "ms_per_step", "steps", "warmup", "config", "roofline", "launch_kinds", "extractor_mfma_tflops",
+            "extractor_frac_of_bf16_peak", "stages")
+    d = {k: res[k] for k in keep if k in res}
+    d["unit"] = "images/s"
+    return d
+
+
+def bench_resident(env, name: str, steps: int, warmup: int, cpu_sample: int, stage_kernels: bool) -> dict:
+    """qrm_detect over one configuration's full batch resident in device memory."""
+    args, np, torch, synth, q = (env[k] for k in ("args", "np", "torch", "synth", "q"))
+    cfg = synth.CONFIGS[name]
     N = args.images or cfg.n_images
-    if args.config == "C4" and not args.images:
-        N = 4096                                   # 16384 x 768 KiB of host staging is needless for timing
     wts = synth.config_weights(cfg)
     ctx = q.Context(weights=wts, rs=dict(m=cfg.m, prim_poly=cfg.prim_poly, n=cfg.n, k=cfg.k, fcr=cfg.fcr))
     if args.micro_batch:
         ctx.qrm_set_micro_batch(args.micro_batch)
 
-    # ---- inputs: seeded, generated on the host in chunks, resident in HBM before the timed region
+    # ---- inputs: seeded, generated on the host in chunks (all host threads), resident in HBM before the timed region
+    log(f"{name}: generating {N} images of 3x{cfg.H}x{cfg.W}")
     d_img = torch.empty((N, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
-    chunk = 256
+    chunk = max(1, (1 << 30) // (3 * cfg.H * cfg.W))
+    stage = torch.empty((min(chunk, N), 3, cfg.H, cfg.W), dtype=torch.uint8, pin_memory=True)
+    first_imgs = None
     for s in range(0, N, chunk):
         c = min(chunk, N - s)
-        d_img[s:s + c].copy_(torch.from_numpy(synth.images(cfg, s, c)))
+        synth.images(cfg, s, c, out=stage.numpy()[:c], threads=HOST_THREADS)
+        if s == 0 and cpu_sample > 0:
+            first_imgs = stage.numpy()[:min(cpu_sample, c)].copy()
+        d_img[s:s + c].copy_(stage[:c])
+        torch.cuda.synchronize()
+    del stage
     off = synth.offsets(cfg, 0, N, args.policy)
     d_off = torch.from_numpy(off).cuda()
     d_logits = torch.empty((N, cfg.n_bits), dtype=torch.float32, device="cuda")
@@ -97,38 +185,110 @@ def main() -> int:
         cal_dst.copy_(cal_src)
         torch.cuda.synchronize()
         del cal_src, cal_dst
-    for _ in range(args.warmup):
+    log(f"{name}: {warmup} warm-up + {steps} timed steps")
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    value = N * args.steps / dt
+    ms_per_step = dt * 1e3 / steps
+    value = N * steps / dt
 
-    # ---- roofline of the dominant kernel: same steps again, every launch bracketed by HIP events
+    # ---- every kind of launch, bracketed by HIP events on the launch stream: a second pass of the same steps
+    prof_steps = min(steps, 5)
     ctx.qrm_profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(prof_steps):
         step()
     torch.cuda.synchronize()
-    k_ms, k_launches, k_flops, blocks_per_launch = ctx.qrm_profile_read()
+    kinds = {}
+    for kind, kname in enumerate(q.binding.PROFILE_KIND_NAMES):
+        ms, launches, flops = ctx.qrm_profile_read(kind)
+        if launches:
+            tfl = flops / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+            kinds[kname] = {"launches_per_step": launches // prof_steps, "avg_launch_us": round(ms * 1e3 / launches, 2),
+                            "ms_per_step": round(ms / prof_steps, 4),
+                            "tflops": round(tfl, 2) if flops else None,
+                            "frac_of_bf16_peak": round(tfl / PEAK_BF16_TFLOPS, 4) if flops else None,
+                            "flops_per_launch": flops / launches if flops else None}
     ctx.qrm_profile_enable(False)
-    achieved_tflops = k_flops / (k_ms * 1e-3) / 1e12 if k_ms > 0 else 0.0
-    kname = ("conv_pair_kernel<64,false,false> (two fused 3x3 conv blocks C->C, bf16 MFMA implicit GEMM, activations between "
-             "them in LDS)") if blocks_per_launch >= 2 else "conv_mid_kernel (3x3 conv C->C, bf16 MFMA implicit GEMM)"
-    roofline = {"kernel": kname, "bound": "mfma",
-                "achieved": round(achieved_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved_tflops / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH if (blocks_per_launch == 2 and args.config == "C2" and not args.micro_batch
-                                                                 and not args.images) else None,
-                "launches": int(k_launches), "avg_launch_us": round(k_ms * 1e3 / max(1, k_launches), 2),
-                "flops_per_launch": k_flops / max(1, k_launches),
-                "sustained_on_random_data": None,   # filled in below: pure matrix loop on random operands
-                "timing": "HIP events around every launch, second pass of the same steps"}
+    conv = {k: v for k, v in kinds.items() if v["tflops"] is not None}
+    dom = max(conv, key=lambda k: conv[k]["ms_per_step"])
+    kernel_names = {
+        "pair_first": "conv_pair_kernel<64,true,false> (crop + normalise + first block + one C->C block, fused)",
+        "pair_mid": "conv_pair_kernel<64,false,false> (two fused 3x3 conv blocks C->C, bf16 MFMA implicit GEMM, activations between them in LDS)",
+        "pair_last": "conv_pair_kernel<64,false,true> (two fused C->C blocks, the second one the network's last: channel sums only)",
+        "block_first": "conv_first_kernel (crop + normalise + conv 3->C)",
+        "block_mid": "conv_mid_kernel (3x3 conv C->C, bf16 MFMA implicit GEMM)",
+        "block_last": "conv_mid_kernel, last block (channel sums only)",
+    }
+    rec = RECORDED_TRAFFIC.get((name, dom))
+    use_rec = bool(rec) and not args.micro_batch and not args.images
+    roofline = {"kernel": kernel_names.get(dom, dom), "bound": "mfma",
+                "achieved": conv[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": conv[dom]["frac_of_bf16_peak"],
+                "traffic": rec["bytes"] if use_rec else None,
+                "traffic_note": (f"recorded, not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at commit "
+                                 f"{rec['commit']} ({rec['source']})") if use_rec else
+                                "no counter run is recorded for this kernel and launch size",
+                "launches_per_step": kinds[dom]["launches_per_step"], "avg_launch_us": kinds[dom]["avg_launch_us"],
+                "flops_per_launch": kinds[dom]["flops_per_launch"],
+                "share_of_step_time": round(kinds[dom]["ms_per_step"] / ms_per_step, 4),
+                "timing": f"HIP events around every launch, a second pass of {prof_steps} steps"}
 
-    # ---- the other two stages on their own (HBM-bound by bytes, in practice latency / ALU bound)
+    l2 = cfg.tile * cfg.tile
+    mfma_flops_per_image = 2 * 9 * 3 * cfg.channels * l2 + (cfg.n_blocks - 1) * 2 * 9 * cfg.channels ** 2 * l2
+    res = {
+        "value": round(value, 1), "ms_per_step": round(ms_per_step, 3), "steps": steps, "warmup": warmup,
+        "config": {"workload": f"{name}: {N} images 3x{cfg.H}x{cfg.W} u8, one {cfg.tile}x{cfg.tile} tile each "
+                               f"({args.policy} origin), {cfg.n_blocks}x conv3x3 {cfg.channels}ch + conv->{cfg.n_bits} "
+                               f"+ pool + linear, RS({cfg.n},{cfg.k}) over GF(2^{cfg.m})",
+                   "images": N, "tile": cfg.tile, "inputs": "resident in HBM before the timed region",
+                   "micro_batch": args.micro_batch or "default"},
+        "roofline": roofline,
+        "launch_kinds": kinds,
+        # MFMA work actually executed per image: first conv + the C -> C convs, over the whole step (all
+        # kernels, launch gaps and the RS decode included in the time).  The final conv + average
+        # pool is evaluated in closed form from nine channel sums of the last block (it is linear), so its
+        # 2*9*C*n_bits*l^2 FLOPs are NOT credited here.
+        "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),
+        "extractor_frac_of_bf16_peak": round(mfma_flops_per_image * value / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "extractor_nominal_tflops_incl_final_conv": round(cfg.flops_per_image() * value / 1e12, 2),
+    }
+    log(f"{name}: {value:.0f} images/s, extractor at {res['extractor_frac_of_bf16_peak']:.3f} of the bf16 peak")
+
+    if stage_kernels:
+        res["stage_kernels"] = bench_stage_kernels(env, ctx, cfg, N, d_img, d_off, stream)
+
+    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not the target)
+    if cpu_sample > 0 and first_imgs is not None:
+        import oracle
+        ns = first_imgs.shape[0]
+        log(f"{name}: CPU oracle on the first {ns} images")
+        t1 = time.perf_counter()
+        ref = oracle.detect(wts, first_imgs, off[:ns], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+        t_cpu = time.perf_counter() - t1
+        cpu = {"value": round(ns / t_cpu, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"first {ns} images of the same {name} batch, whole path (fp64 direct conv + RS)",
+               "seconds": round(t_cpu, 2)}
+        # cheap sanity: the timed GPU outputs for the sample agree with what the oracle just computed
+        g = d_logits[:ns].cpu().numpy().astype(np.float64)
+        err = float((np.abs(g - ref["logits"]) / np.maximum(1.0, np.abs(ref["logits"]))).max())
+        cpu["max_scaled_logit_error_vs_gpu"] = round(err, 5)
+        res["cpu_baseline"] = cpu
+    ctx.close()
+    del d_img
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_stage_kernels(env, ctx, cfg, N, d_img, d_off, stream) -> dict:
+    """The stand-alone kernels of the other stages, each on its own (HBM-bound by bytes; in practice latency, cache
+    or ALU bound as noted)."""
+    args, np, torch, synth, q = (env[k] for k in ("args", "np", "torch", "synth", "q"))
+
     def timed(fn, reps=20):
         fn()
         torch.cuda.synchronize()
@@ -140,22 +300,33 @@ def main() -> int:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e-3
 
+    def entry(t, nbytes, **extra):
+        d = {"us": round(t * 1e6, 2), "algorithmic_GBs": round(nbytes / t / 1e9, 1),
+             "frac_hbm": round(nbytes / t / 1e9 / PEAK_HBM_GBS, 4)}
+        d.update(extra)
+        return d
+
     l2 = cfg.tile * cfg.tile
-    mfma_flops_per_image = 2 * 9 * 3 * cfg.channels * l2 + (cfg.n_blocks - 1) * 2 * 9 * cfg.channels ** 2 * l2
+    out = {}
+    # tile crop: the batch of the configuration (fits the 256 MB Infinity Cache when repeated: not an HBM figure)
+    # and 16 x as many images, beyond any cache, with random and with grid-aligned origins
     d_tiles = torch.empty((N, 3, cfg.tile, cfg.tile), dtype=torch.uint8, device="cuda")
     t_tile = timed(lambda: ctx.qrm_extract_tiles(d_img, N, cfg.H, cfg.W, d_off, cfg.tile, d_tiles, stream=stream))
-    tile_bytes = N * (6 * cfg.tile * cfg.tile + 8)
-    # the same crop on 16 x as many images (4096 crops move 100 MB: a launch of ~12 us at the HBM peak, latency bound)
-    n_big = 16 * N if args.config == "C2" and not args.images else 0
-    t_tile_big = None
-    if n_big:
-        big = torch.empty((n_big, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
-        big.random_(0, 256)
-        big_off = d_off.repeat(16, 1).contiguous()
-        big_tiles = torch.empty((n_big, 3, cfg.tile, cfg.tile), dtype=torch.uint8, device="cuda")
-        t_tile_big = timed(lambda: ctx.qrm_extract_tiles(big, n_big, cfg.H, cfg.W, big_off, cfg.tile, big_tiles,
-                                                         stream=stream), reps=5)
-        del big, big_tiles, big_off
+    tile_bytes = N * (6 * l2 + 8)
+    out["tile_crop"] = entry(t_tile, tile_bytes, images=N,
+                             note="repeated over the same 0.8 GB of images: partly served by the Infinity Cache, not an HBM figure")
+    n_big = 16 * N
+    big = torch.empty((n_big, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
+    big.random_(0, 256)
+    big_tiles = torch.empty((n_big, 3, cfg.tile, cfg.tile), dtype=torch.uint8, device="cuda")
+    for policy in ("random", "random_grid"):
+        boff = torch.from_numpy(synth.offsets(cfg, 0, N, policy)).cuda().repeat(16, 1).contiguous()
+        t_big = timed(lambda: ctx.qrm_extract_tiles(big, n_big, cfg.H, cfg.W, boff, cfg.tile, big_tiles, stream=stream), reps=5)
+        out["tile_crop_large_batch" if policy == "random" else "tile_crop_large_batch_grid_aligned"] = entry(
+            t_big, 16 * tile_bytes, images=n_big, origins=policy,
+            note="12.9 GB of images, beyond the cache" + ("; rows of 64 bytes at random byte offsets touch 2-3 memory sectors each"
+                                                          if policy == "random" else "; the paper's default strategy (Table 1)"))
+    del big, big_tiles, boff
     n_cw = 1 << 20
     sym = torch.randint(0, 1 << cfg.m, (n_cw, cfg.n), dtype=torch.uint8, device="cuda")
     m2 = torch.empty((n_cw, cfg.k), dtype=torch.uint8, device="cuda")
@@ -163,21 +334,26 @@ def main() -> int:
     e2 = torch.empty((n_cw,), dtype=torch.int8, device="cuda")
     t_rs = timed(lambda: ctx.qrm_rs_decode(sym, n_cw, m2, c2, e2, stream=stream))
     rs_bytes = n_cw * (2 * cfg.n + cfg.k + 1)
-    # key verification: on stored messages (streaming, k + 5 bytes per word) and inside the decoder's epilogue
-    n_vw = 1 << 24
-    vmsg = torch.randint(0, 1 << cfg.m, (n_vw, cfg.k), dtype=torch.uint8, device="cuda")
-    vmat = torch.empty((n_vw,), dtype=torch.int32, device="cuda")
-    vdet = torch.empty((n_vw,), dtype=torch.uint8, device="cuda")
+    out["rs_decode"] = {"us": round(t_rs * 1e6, 2), "codewords_per_s": round(n_cw / t_rs, 0),
+                        "algorithmic_GBs": round(rs_bytes / t_rs / 1e9, 2),
+                        "frac_hbm": round(rs_bytes / t_rs / 1e9 / PEAK_HBM_GBS, 5), "codewords": n_cw,
+                        "note": "bound by vector ALU and LDS table look-ups, not by memory"}
+    # key verification on stored messages (streaming, k + 5 bytes per word): 2^24 words fit the Infinity Cache,
+    # 2^27 words (2.2 GB) do not
     ctx.qrm_set_key(np.arange(cfg.k, dtype=np.uint8) & ((1 << cfg.m) - 1),
                     q.binding.qrm_key_threshold(cfg.k * cfg.m, 1e-6))
-    t_vk = timed(lambda: ctx.qrm_verify_key(vmsg, n_vw, vmat, vdet, stream=stream))
-    vk_bytes = n_vw * (cfg.k + 5)
-    del vmsg, vmat, vdet
+    for n_vw, key in ((1 << 24, "verify_key_cache_resident"), (1 << 27, "verify_key")):
+        vmsg = torch.randint(0, 1 << cfg.m, (n_vw, cfg.k), dtype=torch.uint8, device="cuda")
+        vmat = torch.empty((n_vw,), dtype=torch.int32, device="cuda")
+        vdet = torch.empty((n_vw,), dtype=torch.uint8, device="cuda")
+        t_vk = timed(lambda: ctx.qrm_verify_key(vmsg, n_vw, vmat, vdet, stream=stream), reps=10)
+        out[key] = entry(t_vk, n_vw * (cfg.k + 5), words=n_vw, words_per_s=round(n_vw / t_vk, 0))
+        del vmsg, vmat, vdet
     # variance-based tile selection: reads every pixel once (all of the image lies under some window)
     sel_off = torch.empty((N, 2), dtype=torch.int32, device="cuda")
     t_sel = timed(lambda: ctx.qrm_select_tiles_variance(d_img, N, cfg.H, cfg.W, cfg.tile, cfg.tile // 2, sel_off,
                                                         None, stream=stream))
-    sel_bytes = N * (3 * cfg.H * cfg.W + 8)
+    out["select_tiles_variance"] = entry(t_sel, N * (3 * cfg.H * cfg.W + 8), images=N, images_per_s=round(N / t_sel, 0))
     # fused pre-processing from raw 2H x 2W interleaved images: the whole image, and only each image's tile
     n_raw = min(N, 2048)
     raw = torch.randint(0, 256, (n_raw, 2 * cfg.H, 2 * cfg.W, 3), dtype=torch.uint8, device="cuda")
@@ -186,107 +362,42 @@ def main() -> int:
     t_pre_full = timed(lambda: ctx.qrm_preprocess(raw, n_raw, 2 * cfg.H, 2 * cfg.W, cfg.H, None, 0, pre_full, stream=stream))
     t_pre_tile = timed(lambda: ctx.qrm_preprocess(raw, n_raw, 2 * cfg.H, 2 * cfg.W, cfg.H, d_off, cfg.tile, pre_tile,
                                                   stream=stream))
-    pre_full_bytes = n_raw * (4 * 3 * cfg.H * cfg.W + 3 * cfg.H * cfg.W)
-    pre_tile_bytes = n_raw * (4 * 3 * l2 + 3 * l2 + 8)
+    out["preprocess_whole_image"] = entry(t_pre_full, n_raw * (4 * 3 * cfg.H * cfg.W + 3 * cfg.H * cfg.W), images=n_raw,
+                                          images_per_s=round(n_raw / t_pre_full, 0))
+    out["preprocess_tile_only"] = entry(t_pre_tile, n_raw * (4 * 3 * l2 + 3 * l2 + 8), images=n_raw,
+                                        images_per_s=round(n_raw / t_pre_tile, 0))
     # a yardstick for the stages above: the same box's plain device copy of the raw images' volume (read + write)
     cp_dst = torch.empty_like(raw)
     t_copy = timed(lambda: cp_dst.copy_(raw))
-    copy_bytes = 2 * raw.numel()
+    out["device_copy"] = {"us": round(t_copy * 1e6, 2), "GBs_read_plus_write": round(2 * raw.numel() / t_copy / 1e9, 1),
+                          "frac_hbm": round(2 * raw.numel() / t_copy / 1e9 / PEAK_HBM_GBS, 4),
+                          "note": "torch copy_ of the raw-image buffer: what a plain read + write stream reaches here"}
     del raw, pre_full, pre_tile, cp_dst
     # what the matrix pipes sustain with nothing else running, by operand data (the clock follows the power budget)
-    matrix_probe = {"zeros_tflops": round(ctx.qrm_matrix_rate_probe(0), 1),
-                    "random_data_tflops": round(ctx.qrm_matrix_rate_probe(2), 1),
-                    "note": "back-to-back bf16 32x32x16 matrix instructions, 8 wavefronts per CU, no memory traffic"}
-    if isinstance(roofline, dict) and roofline.get("bound") == "mfma":
-        roofline["sustained_on_random_data"] = {"tflops": matrix_probe["random_data_tflops"],
-                                                 "frac_of_it": round(roofline["achieved"] / matrix_probe["random_data_tflops"], 4)}
-    stages = {
-        "matrix_pipe_probe": matrix_probe,
-        "device_copy": {"us": round(t_copy * 1e6, 2), "GBs_read_plus_write": round(copy_bytes / t_copy / 1e9, 1),
-                        "frac_hbm": round(copy_bytes / t_copy / 1e9 / PEAK_HBM_GBS, 4),
-                        "note": "torch copy_ of the raw-image buffer: what a plain read + write stream reaches here"},
-        "preprocess_whole_image": {"us": round(t_pre_full * 1e6, 2), "images_per_s": round(n_raw / t_pre_full, 0),
-                                   "algorithmic_GBs": round(pre_full_bytes / t_pre_full / 1e9, 1),
-                                   "frac_hbm": round(pre_full_bytes / t_pre_full / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},
-        "preprocess_tile_only": {"us": round(t_pre_tile * 1e6, 2), "images_per_s": round(n_raw / t_pre_tile, 0),
-                                 "algorithmic_GBs": round(pre_tile_bytes / t_pre_tile / 1e9, 1),
-                                 "frac_hbm": round(pre_tile_bytes / t_pre_tile / 1e9 / PEAK_HBM_GBS, 4), "images": n_raw},
-        "select_tiles_variance": {"us": round(t_sel * 1e6, 2), "images_per_s": round(N / t_sel, 0),
-                                  "algorithmic_GBs": round(sel_bytes / t_sel / 1e9, 1),
-                                  "frac_hbm": round(sel_bytes / t_sel / 1e9 / PEAK_HBM_GBS, 4), "images": N},
-        "verify_key": {"us": round(t_vk * 1e6, 2), "words_per_s": round(n_vw / t_vk, 0),
-                       "algorithmic_GBs": round(vk_bytes / t_vk / 1e9, 1),
-                       "frac_hbm": round(vk_bytes / t_vk / 1e9 / PEAK_HBM_GBS, 4), "words": n_vw},
-        "tile_crop": {"us": round(t_tile * 1e6, 2), "algorithmic_GBs": round(tile_bytes / t_tile / 1e9, 1),
-                      "frac_hbm": round(tile_bytes / t_tile / 1e9 / PEAK_HBM_GBS, 4), "images": N},
-        "tile_crop_large_batch": None if not t_tile_big else {
-            "us": round(t_tile_big * 1e6, 2), "algorithmic_GBs": round(16 * tile_bytes / t_tile_big / 1e9, 1),
-            "frac_hbm": round(16 * tile_bytes / t_tile_big / 1e9 / PEAK_HBM_GBS, 4), "images": n_big},
-        "rs_decode": {"us": round(t_rs * 1e6, 2), "codewords_per_s": round(n_cw / t_rs, 0),
-                      "algorithmic_GBs": round(rs_bytes / t_rs / 1e9, 2),
-                      "frac_hbm": round(rs_bytes / t_rs / 1e9 / PEAK_HBM_GBS, 5), "codewords": n_cw},
-        # MFMA work actually executed per image: first conv + the C -> C convs, over the whole step (all
-        # kernels, launch gaps and the RS decode included in the time).  The final conv + average
-        # pool is evaluated in closed form from nine channel sums of the last block (it is linear), so its
-        # 2*9*C*n_bits*l^2 FLOPs are NOT credited here.
-        "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),
-        "extractor_frac_of_bf16_peak": round(mfma_flops_per_image * value / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "extractor_nominal_tflops_incl_final_conv": round(cfg.flops_per_image() * value / 1e12, 2),
-    }
-
-    # ---- CPU oracle on a bounded sample of the same workload (reported baseline, not the target)
-    cpu = None
-    if args.cpu_sample > 0:
-        import oracle
-        ns = min(args.cpu_sample, N)
-        imgs = d_img[:ns].cpu().numpy()
-        t1 = time.perf_counter()
-        ref = oracle.detect(wts, imgs, off[:ns], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
-        t_cpu = time.perf_counter() - t1
-        cpu = {"value": round(ns / t_cpu, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"first {ns} images of the same {args.config} batch, whole path (fp64 direct conv + RS)",
-               "seconds": round(t_cpu, 2)}
-        # cheap sanity: the timed GPU outputs for the sample agree with what the oracle just computed
-        g = d_logits[:ns].cpu().numpy().astype(np.float64)
-        err = float((np.abs(g - ref["logits"]) / np.maximum(1.0, np.abs(ref["logits"]))).max())
-        cpu["max_scaled_logit_error_vs_gpu"] = round(err, 5)
-
-    out = {
-        "metric": "images/sec end-to-end detection on 1 MI355X",
-        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.config}: {N} images 3x{cfg.H}x{cfg.W} u8, one {cfg.tile}x{cfg.tile} tile each "
-                               f"({args.policy} origin), {cfg.n_blocks}x conv3x3 {cfg.channels}ch + conv->{cfg.n_bits} "
-                               f"+ pool + linear, RS({cfg.n},{cfg.k}) over GF(2^{cfg.m})",
-                   "images": N, "tile": cfg.tile, "inputs": "resident in HBM before the timed region",
-                   "micro_batch": args.micro_batch or "default"},
-        "roofline": roofline,
-        "stages": stages,
-        "cpu_baseline": cpu,
-        "context": "paper: 2.43x over its sequential baseline; Stable Signature ~30 min per 1M 256x256 images "
-                   "(~556 img/s) on 1x H100 + EPYC 9534 (context only, other hardware)",
-    }
-    print(json.dumps(out))
-    ctx.close()
-    return 0
+    out["matrix_pipe_probe"] = {"zeros_tflops": round(ctx.qrm_diag_matrix_rate(0), 1),
+                                "random_data_tflops": round(ctx.qrm_diag_matrix_rate(2), 1),
+                                "note": "back-to-back bf16 32x32x16 matrix instructions, 8 wavefronts per CU, no memory traffic"}
+    return out
 
 
-def bench_stream(args, cfg, torch, np, synth, q) -> int:
+def bench_stream(env, passes: int, warm_passes: int) -> dict:
     """Streaming configuration: images start in pinned HOST memory; upload, kernels and result download of
     different chunks overlap on the library's own streams (qrm_detect_host).  Three pre-generated chunks
     are recycled, so nothing is generated inside the timed region.  The number is bound by the host
-    link, not by the GPU: the bare pinned upload rate is measured beside it."""
+    link, not by the GPU: the bare pinned upload rate of the same chunks is measured beside it."""
+    args, np, torch, synth, q = (env[k] for k in ("args", "np", "torch", "synth", "q"))
+    cfg = synth.CONFIGS["C5"]
     chunk, n_chunks, lanes = args.chunk_images, args.chunks, args.streams
     wts = synth.config_weights(cfg)
     ctx = q.Context(weights=wts, rs=dict(m=cfg.m, prim_poly=cfg.prim_poly, n=cfg.n, k=cfg.k, fcr=cfg.fcr))
     if args.micro_batch:
         ctx.qrm_set_micro_batch(args.micro_batch)
     n_buf = min(3, n_chunks)
+    log(f"C5: generating {n_buf} pinned chunks of {chunk} images")
     bufs = [torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, pin_memory=True) for _ in range(n_buf)]
     obufs = [torch.empty((chunk, 2), dtype=torch.int32, pin_memory=True) for _ in range(n_buf)]
     for b in range(n_buf):
-        synth.images(cfg, b * chunk, chunk, out=bufs[b].numpy())
+        synth.images(cfg, b * chunk, chunk, out=bufs[b].numpy(), threads=HOST_THREADS)
         obufs[b].copy_(torch.from_numpy(synth.offsets(cfg, b * chunk, chunk, args.policy)))
     n_total = n_chunks * chunk
     h_msg = torch.empty((n_total, cfg.k), dtype=torch.uint8, pin_memory=True)
@@ -297,15 +408,16 @@ def bench_stream(args, cfg, torch, np, synth, q) -> int:
         ctx.qrm_detect_host([bufs[b] for b in order], chunk, cfg.H, cfg.W, [obufs[b] for b in order], cfg.tile, lanes,
                             h_msg, None, h_ne)          # returns when every chunk is done
 
-    for _ in range(args.warmup):
+    log(f"C5: {warm_passes} warm-up + {passes} timed passes of {n_chunks} chunks")
+    for _ in range(warm_passes):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(passes):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    value = n_total * args.steps / dt
+    value = n_total * passes / dt
     # the link on its own: the same chunks uploaded back to back, nothing else running
     d_stage = torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
     d_stage.copy_(bufs[0], non_blocking=True)
@@ -328,10 +440,10 @@ def bench_stream(args, cfg, torch, np, synth, q) -> int:
         ctx.qrm_detect(d_stage, chunk, cfg.H, cfg.W, d_off, cfg.tile, None, None, d_msg, None, d_ne)
     torch.cuda.synchronize()
     resident = 3 * chunk / (time.perf_counter() - t2)
-    out = {
-        "metric": "images/sec end-to-end detection on 1 MI355X", "value": round(value, 1), "unit": "images/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt * 1e3 / args.steps, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    l2 = cfg.tile * cfg.tile
+    mfma_flops_per_image = 2 * 9 * 3 * cfg.channels * l2 + (cfg.n_blocks - 1) * 2 * 9 * cfg.channels ** 2 * l2
+    res = {
+        "value": round(value, 1), "steps": passes, "warmup": warm_passes, "ms_per_step": round(dt * 1e3 / passes, 3),
         "config": {"workload": f"C5 (streamed): {n_chunks} chunks x {chunk} images 3x{cfg.H}x{cfg.W} u8 per step from "
                                f"pinned host memory ({n_buf} buffers recycled), {lanes} chunks in flight; one {cfg.tile}x{cfg.tile} "
                                f"tile each, {cfg.n_blocks}x conv3x3 {cfg.channels}ch, RS({cfg.n},{cfg.k}) over GF(2^{cfg.m})",
@@ -340,13 +452,16 @@ def bench_stream(args, cfg, torch, np, synth, q) -> int:
                      "peak": round(link_gbs, 2), "unit": "GB/s",
                      "frac": round(value * 3 * cfg.H * cfg.W / 1e9 / link_gbs, 4), "traffic": None,
                      "note": "peak = bare pinned upload of the same chunks measured in this run (not a published figure)"},
+        "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),
+        "extractor_frac_of_bf16_peak": round(mfma_flops_per_image * value / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stages": {"bare_upload_GBs": round(link_gbs, 2), "bare_upload_images_per_s": round(link_gbs * 1e9 / (3 * cfg.H * cfg.W), 1),
                    "resident_images_per_s": round(resident, 1)},
-        "cpu_baseline": None,
     }
-    print(json.dumps(out))
+    log(f"C5: {value:.0f} images/s = {res['roofline']['frac']:.3f} of the bare upload rate ({link_gbs:.1f} GB/s)")
     ctx.close()
-    return 0
+    del bufs, d_stage
+    torch.cuda.empty_cache()
+    return res
 
 
 if __name__ == "__main__":

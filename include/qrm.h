@@ -24,7 +24,12 @@
  *   - N == 0 is a successful no-op.
  *   - A context belongs to one device and one host thread at a time.  Work on
  *     up to QRM_MAX_STREAMS different streams may be in flight: each stream
- *     gets its own workspace inside the context.
+ *     gets its own workspace inside the context and keeps it from call to
+ *     call.  When more streams than that have been used, a stream not seen
+ *     before takes over the workspace whose last call lies furthest back; its
+ *     work is ordered (on the device) behind that call, so results stay
+ *     correct, and streams that no longer exist cost nothing.
+ *     qrm_release_stream hands a stream's workspace back explicitly.
  */
 #ifndef QRM_H
 #define QRM_H
@@ -91,7 +96,7 @@ typedef struct {
     int32_t m;          /* 2..8 */
     uint32_t prim_poly; /* e.g. 0x13 for m=4, 0x11D for m=8; must be primitive */
     int32_t n, k;       /* 0 < k < n <= 2^m - 1, n - k even, (n-k)/2 <= 8 */
-    int32_t fcr;        /* first consecutive root, >= 0 (1 in the benchmark configurations) */
+    int32_t fcr;        /* first consecutive root, >= 0 (1 in the benchmark configurations); taken mod 2^m - 1 */
 } qrm_rs_desc;
 
 /*
@@ -117,6 +122,13 @@ QRM_API const char *qrm_last_error(const qrm_ctx *ctx);
  * e.g. 1024 images for 64 x 64 tiles and 64 channels.
  */
 QRM_API qrm_status qrm_set_micro_batch(qrm_ctx *ctx, int32_t images);
+
+/*
+ * Tells the context that `stream` will not be used with it again (e.g. before the caller destroys the
+ * stream): waits for the context's last call on that stream and marks its workspace free for another
+ * stream; the memory is kept for reuse.  A stream the context has never seen is a successful no-op.
+ */
+QRM_API qrm_status qrm_release_stream(qrm_ctx *ctx, void *stream);
 
 /* Bytes of device workspace one stream of this context needs for a call with these sizes. */
 QRM_API size_t qrm_workspace_bytes(const qrm_ctx *ctx, int64_t N, int32_t tile_h, int32_t tile_w);
@@ -174,7 +186,8 @@ QRM_API qrm_status qrm_select_tiles_variance(qrm_ctx *ctx, const uint8_t *d_imag
  * Extractor forward pass on raw tiles (Section 4.1, m' = H_D(tile); hard bit = (logit > 0)).
  * d_tiles u8 [N,3,h,w] raw bytes, normalised inside the first convolution.
  * d_logits f32 [N,n_bits]; d_bits u8 [N,n_bits] with values 0/1, may be NULL.
- * Errors: QRM_E_INVALID (no extractor in ctx, NULL pointer, h or w < 1), QRM_E_NOMEM.
+ * Errors: QRM_E_INVALID (no extractor in ctx, NULL pointer, h or w < 1), QRM_E_UNSUPPORTED (the
+ * activations of one tile, h*w*channels*2 bytes, exceed 1900 MiB), QRM_E_NOMEM.
  */
 QRM_API qrm_status qrm_extractor_forward(qrm_ctx *ctx, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w,
                                  float *d_logits, uint8_t *d_bits, void *stream);
@@ -200,9 +213,9 @@ QRM_API qrm_status qrm_rs_decode(qrm_ctx *ctx, const uint8_t *d_symbols, int64_t
                          uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
 
 /*
- * The whole detection path on a batch resident in device memory: crop + normalise fused into the
- * first convolution, extractor, threshold, MSB-first bit->symbol packing (symbol j = bits
- * j*m .. j*m+m-1), RS decode.  Requires n_bits == n*m.
+ * The whole detection path of Section 4.3 ("Detection with Reed-Solomon Correction") on a batch resident
+ * in device memory: crop + normalise fused into the first convolution, extractor, threshold, MSB-first
+ * bit->symbol packing (symbol j = bits j*m .. j*m+m-1), RS decode.  Requires n_bits == n*m.
  * d_images u8 [N,3,H,W]; d_off_yx i32 [N,2] or NULL; tile = l.
  * d_logits f32 [N,n_bits] or NULL; d_bits u8 [N,n_bits] or NULL;
  * d_msg u8 [N,k]; d_codeword u8 [N,n] or NULL; d_nerr i8 [N].
@@ -269,28 +282,27 @@ QRM_API qrm_status qrm_detect_host(qrm_ctx *ctx, const uint8_t *const *h_chunks,
                                    uint8_t *h_msg, uint8_t *h_codeword, int8_t *h_nerr);
 
 /*
- * Per-launch timing of the dominant kernel, for benchmarks: while enabled, every launch of that kernel is
- * bracketed by two hipEvents recorded on the stream it is launched on.  The dominant kernel is the fused
- * pair of C -> C convolution blocks when the configuration runs any (64 channels, tiles up to 64 wide),
- * otherwise the single C -> C convolution block.  qrm_profile_read waits for the recorded events, returns
- * the summed duration in milliseconds, the number of launches and their algorithmic FLOPs (2*9*C*C*h*w
- * per image and block) and the number of blocks one timed launch computes (1 or 2), and clears the record.
- * Any output pointer may be NULL.
+ * Per-launch timing, for benchmarks: while enabled, every kernel launch of qrm_detect / qrm_detect_verify /
+ * qrm_extractor_forward on this context is bracketed by two hipEvents recorded on the stream it is launched
+ * on, and filed under one of the kinds below.  qrm_profile_enable(ctx, on) switches the recording and clears
+ * what was recorded.  qrm_profile_read waits for the recorded events of one kind and returns their summed
+ * duration in milliseconds, the number of launches and their algorithmic FLOPs (2*9*C_in*C_out*h*w per image
+ * and convolution block; 0 for the kinds that are not convolutions); it does not clear.  Any output pointer
+ * may be NULL.  Errors: QRM_E_INVALID for a kind outside 0..QRM_PROFILE_KINDS-1.
  */
+enum {
+    QRM_PROFILE_PAIR_FIRST = 0,  /* fused launch: the network's first block + the C -> C block after it */
+    QRM_PROFILE_PAIR_MID = 1,    /* fused launch: two C -> C blocks, activations written */
+    QRM_PROFILE_PAIR_LAST = 2,   /* fused launch whose second block is the network's last (channel sums only) */
+    QRM_PROFILE_BLOCK_FIRST = 3, /* the first block alone */
+    QRM_PROFILE_BLOCK_MID = 4,   /* one C -> C block alone */
+    QRM_PROFILE_BLOCK_LAST = 5,  /* the last block alone */
+    QRM_PROFILE_HEAD = 6,        /* final convolution + pool + linear + threshold + symbol packing */
+    QRM_PROFILE_RS_DECODE = 7,   /* Reed-Solomon decoding */
+    QRM_PROFILE_KINDS = 8
+};
 QRM_API qrm_status qrm_profile_enable(qrm_ctx *ctx, int32_t on);
-QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, double *ms_total, int64_t *launches, double *flops,
-                                    int32_t *blocks_per_launch);
-
-/*
- * Diagnostic for benchmarks: the rate the matrix pipes sustain when nothing else runs - eight wavefronts per
- * compute unit issuing the bf16 32x32x16 matrix instruction back to back for a few milliseconds - on operands
- * of the given kind: data = 0 zeros, 1 one constant, 2 random (one side small normal values like weights, the
- * other half zeros and half positive like activations after a ReLU).  The part's clock follows its power
- * budget and the power of a matrix instruction follows its data, so the third figure, not the published
- * peak, is what a convolution on real activations can approach.  *tflops receives 10^12 FLOP/s.
- * Allocates and frees a small scratch buffer; synchronises the device's default stream.
- */
-QRM_API qrm_status qrm_matrix_rate_probe(qrm_ctx *ctx, int32_t data, double *tflops);
+QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, int32_t kind, double *ms_total, int64_t *launches, double *flops);
 
 /* Library version string, e.g. "qrm 0.1 gfx950". */
 QRM_API const char *qrm_version(void);

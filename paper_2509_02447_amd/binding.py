@@ -40,7 +40,13 @@ class _RsDesc(C.Structure):
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
            "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
-           "qrm_profile_enable", "qrm_profile_read", "qrm_matrix_rate_probe", "qrm_version"]
+           "qrm_profile_enable", "qrm_profile_read", "qrm_release_stream", "qrm_version"]
+DIAG_EXPORTS = ["qrm_diag_set_flags", "qrm_diag_matrix_rate"]      # include/qrm_diag.h: bench and test tooling
+
+QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE = 1, 2
+(QRM_PROFILE_PAIR_FIRST, QRM_PROFILE_PAIR_MID, QRM_PROFILE_PAIR_LAST, QRM_PROFILE_BLOCK_FIRST, QRM_PROFILE_BLOCK_MID,
+ QRM_PROFILE_BLOCK_LAST, QRM_PROFILE_HEAD, QRM_PROFILE_RS_DECODE, QRM_PROFILE_KINDS) = range(9)
+PROFILE_KIND_NAMES = ["pair_first", "pair_mid", "pair_last", "block_first", "block_mid", "block_last", "head", "rs_decode"]
 
 
 def lib_path() -> str:
@@ -93,11 +99,14 @@ def load_library():
     lib.qrm_detect_verify.restype = C.c_int
     lib.qrm_profile_enable.argtypes = [vp, i32]
     lib.qrm_profile_enable.restype = C.c_int
-    lib.qrm_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double),
-                                     C.POINTER(C.c_int32)]
+    lib.qrm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.qrm_profile_read.restype = C.c_int
-    lib.qrm_matrix_rate_probe.argtypes = [vp, i32, C.POINTER(C.c_double)]
-    lib.qrm_matrix_rate_probe.restype = C.c_int
+    lib.qrm_release_stream.argtypes = [vp, vp]
+    lib.qrm_release_stream.restype = C.c_int
+    lib.qrm_diag_set_flags.argtypes = [vp, i32]
+    lib.qrm_diag_set_flags.restype = C.c_int
+    lib.qrm_diag_matrix_rate.argtypes = [vp, i32, C.POINTER(C.c_double)]
+    lib.qrm_diag_matrix_rate.restype = C.c_int
     lib.qrm_version.argtypes = []
     lib.qrm_version.restype = C.c_char_p
     _lib = lib
@@ -212,16 +221,22 @@ class Context:
     def qrm_profile_enable(self, on: bool):
         self._check(self._lib.qrm_profile_enable(self._h, int(bool(on))))
 
-    def qrm_profile_read(self):
-        """-> (milliseconds, launches, algorithmic FLOPs, blocks per launch) of the timed launches since enable."""
-        ms, n, fl, bp = C.c_double(), C.c_int64(), C.c_double(), C.c_int32()
-        self._check(self._lib.qrm_profile_read(self._h, C.byref(ms), C.byref(n), C.byref(fl), C.byref(bp)))
-        return ms.value, n.value, fl.value, bp.value
+    def qrm_profile_read(self, kind: int):
+        """-> (milliseconds, launches, algorithmic FLOPs) of the timed launches of one kind since enable."""
+        ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
+        self._check(self._lib.qrm_profile_read(self._h, int(kind), C.byref(ms), C.byref(n), C.byref(fl)))
+        return ms.value, n.value, fl.value
 
-    def qrm_matrix_rate_probe(self, data: int) -> float:
+    def qrm_release_stream(self, stream=None):
+        self._check(self._lib.qrm_release_stream(self._h, _stream_handle(stream)))
+
+    def qrm_diag_set_flags(self, flags: int):
+        self._check(self._lib.qrm_diag_set_flags(self._h, int(flags)))
+
+    def qrm_diag_matrix_rate(self, data: int) -> float:
         """-> TFLOP/s the matrix pipes sustain on zeros (0), a constant (1) or random operands (2)."""
         v = C.c_double()
-        self._check(self._lib.qrm_matrix_rate_probe(self._h, int(data), C.byref(v)))
+        self._check(self._lib.qrm_diag_matrix_rate(self._h, int(data), C.byref(v)))
         return v.value
 
     def qrm_workspace_bytes(self, N: int, tile_h: int, tile_w: int) -> int:

@@ -4,14 +4,17 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqrm.so")
-SOURCES = ["qrm_api.hip", "extractor.hip", "rs_decode.hip", "tiles.hip"]
-HEADERS = ["qrm_internal.h", os.path.join("..", "..", "include", "qrm.h")]
+OBJ_DIR = os.path.join(HERE, "_build")
+SOURCES = ["qrm_api.hip", "extractor.hip", "rs_decode.hip", "tiles.hip", "qrm_diag.hip"]
+HEADERS = ["qrm_internal.h", os.path.join("..", "..", "include", "qrm.h"),
+           os.path.join("..", "..", "include", "qrm_diag.h")]
 
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          # packed fp32 arithmetic is kept off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -33,13 +36,23 @@ def stale() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source into paper_2509_02447_amd/libqrm.so."""
+    """Compile every HIP source (one hipcc process per file, in parallel) and link paper_2509_02447_amd/libqrm.so."""
     if not force and not stale():
         return LIB
-    cmd = [hipcc()] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
-    if verbose:
-        cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
-    subprocess.check_call(cmd)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    cc = hipcc()
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        cmd = [cc] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
+        subprocess.check_call(cmd)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    subprocess.check_call([cc] + FLAGS + ["-shared"] + objs + ["-o", LIB])
     return LIB
 
 

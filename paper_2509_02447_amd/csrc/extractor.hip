@@ -9,18 +9,23 @@
 //  * Weights are stationary in registers: a wavefront owns 32 output channels and keeps all
 //    9 * C/16 of their A fragments (144 VGPRs at C = 64) for the lifetime of a persistent workgroup.
 //    The folded batch-norm scale is multiplied into the weights at context creation; bias and ReLU are
-//    applied to the accumulators before the single bf16 rounding per layer.
-//  * A workgroup (4 wavefronts) stages a strip of (4+2) x (64+2) pixels, halo included, in LDS (pixel
-//    stride padded by 16 bytes so that the 16-byte fragment reads are bank-conflict free), zero filling
-//    whatever lies outside the tile.  Each fragment read from LDS is used by up to three matrix
-//    instructions (the three vertical taps that touch that input row).
+//    applied to the accumulators on the way out, before the single bf16 rounding per layer.
+//  * Workgroups are persistent (one per compute unit, eight wavefronts in two groups of four) and stage
+//    rows of pixels in LDS rings with direct-to-LDS loads: a pixel takes C * 2 + 16 bytes, so that the
+//    16-byte fragment reads are bank-conflict free, and whatever lies outside the tile is loaded from a
+//    block of zeros.  Each fragment read from LDS feeds up to three matrix instructions (the three
+//    vertical taps that touch that input row).  conv_mid_kernel computes one block per launch (strips of
+//    4 rows x 64 columns, the two groups in opposite phases); conv_pair_kernel computes two consecutive
+//    blocks per launch and keeps the activations between them in a second LDS ring.
 //  * Rows of the weight fragments are permuted so that a lane ends up with 16 consecutive output
 //    channels of one pixel: the epilogue writes two 16-byte stores per lane.
 //  * The first layer reads the u8 image directly (tile crop + normalisation fused: zero padding is
-//    applied in the normalised domain and never looks outside the tile), K = 27 padded to 32.
-//  * The last layer (C -> n_bits, no ReLU) never writes its output: it is summed over pixels in the
-//    accumulators (global average pool), reduced across lanes once per image, and handed to a small
-//    kernel that applies the linear layer, thresholds and packs m-bit symbols.
+//    applied in the normalised domain and never looks outside the tile); K = 9 taps x 4 channels (r, g,
+//    b, 0) = 36, padded to 48, with the weights as bf16 high part + bf16 residual.
+//  * The last block writes no activations when the final convolution has no ReLU: final conv + global
+//    average pool are linear, so nine border-aware channel sums per image are all head_kernel needs to
+//    apply the final convolution (fp32 weights), the linear layer, the threshold and the symbol packing.
+//    With a final ReLU, conv_final_kernel sums the final convolution's output in its accumulators.
 #include "qrm_internal.h"
 
 namespace qrm {
@@ -249,7 +254,7 @@ __device__ __forceinline__ void load_weight_frags(bf16x8 (&Wr)[9][C / 16], const
 //  (1) weights are bf16 on the matrix cores; the rounding residual W - bf16(W) acts on the mean
 //      activation as a constant per output channel, the only part of the rounding error that global
 //      average pooling does not wash out.  The consumer adds sum_c rsum[o][c] * mean[c] to its bias
-//      (rsum = residual summed over the 9 taps), with mean estimated from every fourth strip.
+//      (rsum = residual summed over the 9 taps), with mean estimated from every eighth strip.
 //  (2) the last conv (C -> n_bits, no ReLU) followed by the global average pool is linear, so it only
 //      needs, per channel of the last block's output, the sums over the whole tile, its first / last
 //      row, first / last column and four corners (9 numbers): the last block writes no activations.
@@ -1638,39 +1643,6 @@ hipError_t launch_linear_pack(const float *partial, int n_part, int nbp, int64_t
     if (n_img <= 0) return hipSuccess;
     hipLaunchKernelGGL(linear_pack_kernel, dim3((unsigned)n_img), dim3(128), 0, s, partial, n_part, nbp, n_bits, inv_hw,
                        fbias, lin_w, lin_b, logits, bits, symbols, m);
-    return hipGetLastError();
-}
-
-// Diagnostic: what the matrix pipes sustain with nothing else going on.  Eight wavefronts per CU issue
-// v_mfma_f32_32x32x16_bf16 back to back on four operand sets taken from `src` (8192 floats: 4096 for the A
-// side, 4096 for the B side).  The clock of the part follows its power budget, and the power of a matrix
-// instruction follows the data: zeros run at the published rate, random data do not.
-__global__ __launch_bounds__(512) void matrix_rate_kernel(const float *__restrict__ src, int iters, float *__restrict__ out)
-{
-    bf16x8 a[4], b[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            a[s][i] = (bf16_t)src[((s * 8 + i) * 512 + threadIdx.x) % 4096];
-            b[s][i] = (bf16_t)src[((s * 8 + i) * 512 + threadIdx.x) % 4096 + 4096];
-        }
-    f32x16 acc[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[s][i] = 0.f;
-#pragma unroll 1
-    for (int i = 0; i < iters; ++i) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) acc[s] = mfma32(a[s], b[s], acc[s]);
-    }
-    out[blockIdx.x * 512 + threadIdx.x] = acc[0][0] + acc[1][1] + acc[2][2] + acc[3][3];
-}
-
-hipError_t launch_matrix_rate(const float *src, int iters, int blocks, float *out, hipStream_t s)
-{
-    hipLaunchKernelGGL(matrix_rate_kernel, dim3(blocks), dim3(512), 0, s, src, iters, out);
     return hipGetLastError();
 }
 

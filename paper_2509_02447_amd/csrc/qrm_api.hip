@@ -9,7 +9,8 @@
 #include <vector>
 
 #include <stdlib.h>
-#include "qrm_internal.h"
+#include "qrm_ctx.h"
+#include "../../include/qrm_diag.h"
 
 using namespace qrm;
 
@@ -28,13 +29,6 @@ uint16_t f32_to_bf16_rne(float f)
 
 namespace {
 
-struct Slot {
-    bool used = false;
-    hipStream_t stream = nullptr;
-    void *ws = nullptr;
-    size_t bytes = 0;
-};
-
 std::string g_create_error;
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
@@ -45,51 +39,20 @@ int perm32(int r) { return 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3); }
 
 } // namespace
 
-struct qrm_ctx {
-    int device = 0;
-    int num_cu = 256;
-    bool has_ext = false, has_rs = false;
-    // extractor
-    int n_blocks = 0, C = 0, n_bits = 0, nbp = 0, final_relu = 0, final_affine = 0;
-    float mean[3] = {0, 0, 0}, inv_std[3] = {1, 1, 1};
-    void *d_weights = nullptr;  // one allocation: all fragments, biases, linear layer
-    const bf16_t *d_w_first = nullptr;
-    std::vector<const bf16_t *> d_w_mid;
-    const bf16_t *d_w_final = nullptr;
-    const float *d_bias = nullptr;        // [n_blocks*C]
-    const float *d_bias_final = nullptr;  // [nbp] or null
-    const float *d_lin_w = nullptr, *d_lin_b = nullptr;
-    const float *d_rsum = nullptr;        // [(n_blocks-1)][C][C] weight-rounding residual sums of the C -> C layers
-    const float *d_wft = nullptr;         // final conv, fp32, [C*9][nbp]
-    bool collapse = false;                // final conv + pool evaluated in closed form from channel sums
-    bool pairable = false;                // weights are prepared for the fused schedule (see qrm_create)
-    // code
-    RsParams rs{};
-    void *d_tables = nullptr;             // 1 KiB: antilog table, log table at 512, key symbols at 768
-    bool has_key = false;
-    int key_tau = 0;
-    // workspace
-    int micro_batch = 0; // 0 = default
-    Slot slots[QRM_MAX_STREAMS + 1]; // the caller's streams plus the kernel stream of qrm_detect_host
-    // optional per-launch timing of the C -> C convolution kernel (hipEvents on the launch stream)
-    bool profile = false;
-    std::vector<hipEvent_t> ev_pool;  // pairs: start, stop
-    size_t ev_used = 0;
-    double prof_flops = 0.0;          // algorithmic FLOPs of the timed launches
-    int prof_blocks = 1;              // convolution blocks one timed launch computes (2: fused pair)
-    // chunked host -> device pipeline of qrm_detect_host, created on first use: one stream per role
-    // (upload, kernels, download) and a ring of staging buffers with the events that hand them on
-    struct Stage {
-        uint8_t *d_img = nullptr;  // [chunk,3,H,W]
-        int32_t *d_off = nullptr;  // [chunk,2]
-        uint8_t *d_out = nullptr;  // msg [chunk,k] | codeword [chunk,n] | nerr [chunk]
-        size_t img_bytes = 0, out_bytes = 0, off_bytes = 0;
-        hipEvent_t uploaded = nullptr, computed = nullptr, downloaded = nullptr;
-    };
-    Stage stages[QRM_MAX_STREAMS];
-    hipStream_t s_up = nullptr, s_run = nullptr, s_down = nullptr;
-    std::string err;
-};
+namespace qrm {
+
+qrm_status fail(qrm_ctx *c, qrm_status st, const std::string &msg)
+{
+    if (c) c->err = msg; else g_create_error = msg;
+    return st;
+}
+
+qrm_status hip_fail(qrm_ctx *c, hipError_t e, const char *what)
+{
+    return fail(c, QRM_E_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+} // namespace qrm
 
 namespace {
 
@@ -155,17 +118,6 @@ struct Big {
         return 0;
     }
 };
-
-qrm_status fail(qrm_ctx *c, qrm_status st, const std::string &msg)
-{
-    if (c) c->err = msg; else g_create_error = msg;
-    return st;
-}
-
-qrm_status hip_fail(qrm_ctx *c, hipError_t e, const char *what)
-{
-    return fail(c, QRM_E_DEVICE, std::string(what) + ": " + hipGetErrorString(e));
-}
 
 // ---- weights -> MFMA A-fragment order ------------------------------------------------------------
 // fragment element (blk, tap, kc, lane, e): output channel blk*32 + perm32(lane%32),
@@ -250,13 +202,16 @@ void residual_sums(const float *w, const float *scale, const std::vector<uint16_
         }
 }
 
+// One image's activations must stay below this many bytes: the kernels address a pixel inside an image with
+// 32-bit byte offsets.
+constexpr size_t kMaxImageActBytes = (size_t)1900 << 20;
+
 int default_micro_batch(const qrm_ctx *c, int h, int w)
 {
     // Half a GiB of activations per buffer: measured best for the fused pairs (1024 images at 64 x 64: four per
     // compute unit, which the workgroups walk through without draining) and for the single-block kernel on wide
     // tiles (256 images at 128 x 128, 64 at 256 x 256: ~16 k strips per launch).  Cache residency of the two
     // buffers (128 MiB each) measured worse in both cases.
-    (void)w;
     const size_t per_img = (size_t)h * w * c->C * 2;
     size_t mb = ((size_t)512 << 20) / (per_img ? per_img : 1);
     if (mb < 64) mb = 64;
@@ -264,38 +219,38 @@ int default_micro_batch(const qrm_ctx *c, int h, int w)
     return (int)mb;
 }
 
-int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w)
+int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w, size_t act_budget)
 {
-    int mb = c->micro_batch > 0 ? c->micro_batch : default_micro_batch(c, h, w);
-    if ((int64_t)mb > N) mb = (int)(N > 0 ? N : 1);
-    // the kernels address both activation buffers with 32-bit byte offsets from the workspace base
     const size_t per_img = (size_t)h * w * c->C * 2;
-    const size_t cap = ((size_t)1900 << 20) / (per_img ? per_img : 1);
-    if ((size_t)mb > cap) mb = (int)(cap > 0 ? cap : 1);
-    return mb;
+    int mb = c->micro_batch > 0 ? c->micro_batch : default_micro_batch(c, h, w);
+    if (act_budget) mb = (int)std::min<size_t>(act_budget / (per_img ? per_img : 1), 65536);
+    if ((int64_t)mb > N) mb = (int)(N > 0 ? N : 1);
+    // the single-block kernels address both activation buffers with 32-bit byte offsets from the workspace base
+    const size_t cap = kMaxImageActBytes / (per_img ? per_img : 1);
+    if ((size_t)mb > cap) mb = (int)cap;
+    return mb; // 0: not even one image fits
 }
-
-struct WsLayout {
-    size_t act, partial, stats, symbols, total;
-    int mb, n_part;
-};
 
 int tiles_per_image(int h, int w) { return ((h + kRows - 1) / kRows) * ((w + kTileW - 1) / kTileW); }
 int first_blocks(const qrm_ctx *c) { return 8 * c->num_cu; }
 int mid_blocks(const qrm_ctx *c) { return c->num_cu; } // one persistent workgroup per CU
 
-WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
+} // namespace
+
+namespace qrm {
+
+WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols, size_t act_budget)
 {
     WsLayout L{};
     if (c->has_ext) {
-        L.mb = effective_micro_batch(c, N, h, w);
+        L.mb = effective_micro_batch(c, N, h, w, act_budget);
         L.n_part = ((w + kTileW - 1) / kTileW) * 2;
         L.act = align_up((size_t)L.mb * h * w * c->C * 2);
         L.partial = align_up((size_t)L.mb * L.n_part * c->nbp * 4);
         // statistics records: sized for the fullest micro-batch and for the ragged last one
         const int tpi = tiles_per_image(h, w);
         size_t recs = 0;
-        const int64_t counts[2] = {L.mb, N % L.mb};
+        const int64_t counts[2] = {L.mb, L.mb ? N % L.mb : 0};
         for (int64_t cnt : counts) {
             if (cnt <= 0) continue;
             const Partition pf = make_partition(cnt, tpi, first_blocks(c));
@@ -307,22 +262,46 @@ WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols)
         L.stats = align_up(recs * stat_record_floats(c->C, 9) * 4);
     }
     L.symbols = (want_symbols && c->has_rs) ? align_up((size_t)N * c->rs.n) : 0;
-    L.total = kZeroBytes + 2 * L.act + L.partial + 2 * L.stats + L.symbols;
+    L.total = kZeroBytes + 2 * L.act + L.partial + 2 * L.stats + L.seam + L.symbols;
     return L;
 }
 
-qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
+} // namespace qrm
+
+namespace {
+
+// Hands the caller's stream its workspace of at least `bytes` bytes.  A stream keeps its workspace from call
+// to call.  A stream not seen before takes a free one, or - when all are taken - the one whose last call lies
+// furthest back: the new stream is then made to wait (on the device) for that call to finish, so nothing is
+// overwritten while in use, whether or not the old stream still exists.
+qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, QrmSlot **out)
 {
-    Slot *slot = nullptr;
+    QrmSlot *slot = nullptr;
     for (auto &sl : c->slots)
         if (sl.used && sl.stream == s) { slot = &sl; break; }
-    if (!slot)
-        for (auto &sl : c->slots)
-            if (!sl.used) { slot = &sl; slot->used = true; slot->stream = s; break; }
-    if (!slot) return fail(c, QRM_E_UNSUPPORTED, "more than QRM_MAX_STREAMS caller streams used with one context");
+    if (!slot) {
+        for (auto &sl : c->slots) // a free one, preferably one whose memory is already large enough
+            if (!sl.used && (!slot || (slot->bytes < bytes && sl.bytes > slot->bytes))) slot = &sl;
+        if (!slot)
+            for (auto &sl : c->slots)
+                if (!slot || sl.last_use < slot->last_use) slot = &sl;
+        if (slot->done && slot->last_use) {
+            hipError_t e = hipStreamWaitEvent(s, slot->done, 0);
+            if (e != hipSuccess) return hip_fail(c, e, "hipStreamWaitEvent(workspace hand-over)");
+        }
+        slot->used = true;
+        slot->stream = s;
+    }
+    slot->last_use = ++c->use_clock;
+    if (!slot->done) {
+        hipError_t e = hipEventCreateWithFlags(&slot->done, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(c, e, "hipEventCreateWithFlags");
+    }
     if (slot->bytes < bytes) {
         if (slot->ws) {
-            hipError_t e = hipStreamSynchronize(s);
+            // everything that used the old memory is behind `done` (calls on earlier streams) or on s itself
+            hipError_t e = hipEventSynchronize(slot->done);
+            if (e == hipSuccess) e = hipStreamSynchronize(s);
             if (e != hipSuccess) return hip_fail(c, e, "hipStreamSynchronize");
             (void)hipFree(slot->ws);
             slot->ws = nullptr;
@@ -336,10 +315,9 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
             return fail(c, QRM_E_NOMEM, buf);
         }
         slot->bytes = bytes;
-        // Debugging aid: QRM_POISON_WORKSPACE=1 fills a new workspace with 0xFF bytes (NaN as bf16 / fp32),
-        // so that a kernel reading something no kernel wrote shows up in the results.
-        static const bool poison = getenv("QRM_POISON_WORKSPACE") != nullptr;
-        if (poison) {
+        // Diagnostic (qrm_diag_set_flags): a new workspace filled with 0xFF bytes (NaN as bf16 / fp32), so that
+        // a kernel reading something no kernel wrote shows up in the results.
+        if (c->diag_flags & QRM_DIAG_POISON_WORKSPACE) {
             e = hipMemsetAsync(slot->ws, 0xFF, bytes, s);
             if (e != hipSuccess) return hip_fail(c, e, "hipMemsetAsync(workspace poison)");
         }
@@ -352,12 +330,43 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, Slot **out)
     return QRM_OK;
 }
 
-// Runs the extractor over [N] tiles taken from `src` (whole images + origins, or raw tiles).
-// n_run < 0: full pass -> logits / bits / symbols.  n_run >= 1: stop after that many blocks -> d_act.
-qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src, int64_t N, int h, int w, int n_run,
-                         float *d_logits, uint8_t *d_bits, uint8_t *d_symbols, int m_sym, float *d_act, hipStream_t s)
+// behind the last kernel of a call: whoever takes the workspace over waits for this
+qrm_status slot_done(qrm_ctx *c, QrmSlot *slot, hipStream_t s)
 {
-    uint8_t *base = (uint8_t *)slot->ws;
+    hipError_t e = hipEventRecord(slot->done, s);
+    if (e != hipSuccess) return hip_fail(c, e, "hipEventRecord");
+    return QRM_OK;
+}
+
+// Event pair around one launch while profiling is on (null otherwise).
+qrm_ctx::Timed *time_begin(qrm_ctx *c, bool may_time, int kind, double flops, hipStream_t s)
+{
+    if (!c->profile || !may_time) return nullptr;
+    if (c->timed_used == c->timed.size()) {
+        qrm_ctx::Timed t;
+        if (hipEventCreate(&t.start) != hipSuccess) return nullptr;
+        if (hipEventCreate(&t.stop) != hipSuccess) { (void)hipEventDestroy(t.start); return nullptr; }
+        c->timed.push_back(t);
+    }
+    qrm_ctx::Timed *t = &c->timed[c->timed_used++];
+    t->kind = kind;
+    t->flops = flops;
+    (void)hipEventRecord(t->start, s);
+    return t;
+}
+void time_end(qrm_ctx::Timed *t, hipStream_t s)
+{
+    if (t) (void)hipEventRecord(t->stop, s);
+}
+
+} // namespace
+
+namespace qrm {
+
+qrm_status run_extractor(qrm_ctx *c, uint8_t *base, const WsLayout &L, TileSrc src, int64_t N, int h, int w, int n_run,
+                         float *d_logits, uint8_t *d_bits, uint8_t *d_symbols, int m_sym, float *d_act, bool may_time,
+                         hipStream_t s)
+{
     const uint32_t buf_off[2] = {(uint32_t)kZeroBytes, (uint32_t)(kZeroBytes + L.act)};
     bf16_t *buf[2] = {(bf16_t *)(base + buf_off[0]), (bf16_t *)(base + buf_off[1])};
     float *partial = (float *)(base + kZeroBytes + 2 * L.act);
@@ -368,6 +377,8 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
     const int32_t *off0 = src.off;
     const int tpi = tiles_per_image(h, w);
     const float inv_hw = 1.0f / ((float)h * (float)w);
+    const double block_flops = 2.0 * 9.0 * c->C * c->C * (double)h * w;   // one C -> C block, one image
+    const double first_flops = 2.0 * 9.0 * 3 * c->C * (double)h * w;      // the first block, one image
     hipError_t e;
     for (int64_t n0 = 0; n0 < N; n0 += L.mb) {
         const int cnt = (int)((N - n0 < L.mb) ? (N - n0) : L.mb);
@@ -379,59 +390,46 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         int cur = 0, tcur = 0, in_slots = pf.slots * pf.sub;
         const int blocks = n_run > 0 ? n_run : c->n_blocks; // blocks to run: the first one and C -> C layers m = b - 1
         // Fused schedule when the tile is a single column block: [first + layer 0], (1,2), (3,4), ..; what is
-        // left over runs alone.  While timing is on, the launches of the dominant kind (fused pairs of C -> C
-        // layers that write activations, if any run, else single C -> C layers) are bracketed by events.
-        static const bool no_pairs = getenv("QRM_DISABLE_PAIRS") != nullptr; // A/B switch for measurements
-        const bool fused = !no_pairs && c->pairable && conv_pair_supported(c->C, g) && blocks >= 2;
-        const bool time_pairs = fused && blocks >= 4;
+        // left over runs alone.
+        const bool fused = !(c->diag_flags & QRM_DIAG_NO_FUSED_PAIRS) && c->pairable && conv_pair_supported(c->C, g) && blocks >= 2;
         auto is_last = [&](int b) { return n_run < 0 && c->collapse && b == c->n_blocks - 1; };
         int b = 1;
         if (fused) {
+            qrm_ctx::Timed *t = time_begin(c, may_time, is_last(1) ? QRM_PROFILE_PAIR_LAST : QRM_PROFILE_PAIR_FIRST,
+                                           (first_flops + block_flops) * cnt, s);
             e = launch_conv_pair(base, 0, &src, g, c->C, c->d_w_first, c->d_w_mid[0], c->d_bias, c->d_bias + (size_t)c->C, nullptr,
                                  0, nullptr, tb[tcur], is_last(1), c->num_cu, buf[cur], s);
             if (e != hipSuccess) return hip_fail(c, e, "conv_pair (first) launch");
+            time_end(t, s);
             in_slots = conv_pair_records_per_image();
             b = 2;
         } else {
+            qrm_ctx::Timed *t = time_begin(c, may_time, QRM_PROFILE_BLOCK_FIRST, first_flops * cnt, s);
             e = launch_conv_first(src, g, c->C, c->d_w_first, c->d_bias, tb[tcur], pf, buf[cur], s);
             if (e != hipSuccess) return hip_fail(c, e, "conv_first launch");
+            time_end(t, s);
         }
         while (b < blocks) {
             const int m = b - 1;
             const bool pair = fused && (m & 1) == 1 && b + 1 < blocks;
-            const bool timed = c->profile && pair == time_pairs && !(pair && time_pairs && is_last(b + 1) && blocks >= 6);
-            hipEvent_t ev1 = nullptr;
-            if (timed) {
-                if (c->ev_used + 2 > c->ev_pool.size()) {
-                    for (int i = 0; i < 2; ++i) {
-                        hipEvent_t ev;
-                        e = hipEventCreate(&ev);
-                        if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
-                        c->ev_pool.push_back(ev);
-                    }
-                }
-                hipEvent_t ev0 = c->ev_pool[c->ev_used];
-                ev1 = c->ev_pool[c->ev_used + 1];
-                c->ev_used += 2;
-                (void)hipEventRecord(ev0, s);
-            }
             const float *rsum = c->d_rsum + (size_t)m * c->C * c->C;
             if (pair) {
+                qrm_ctx::Timed *t = time_begin(c, may_time, is_last(b + 1) ? QRM_PROFILE_PAIR_LAST : QRM_PROFILE_PAIR_MID,
+                                               2.0 * block_flops * cnt, s);
                 e = launch_conv_pair(base, buf_off[cur], nullptr, g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1],
                                      c->d_bias + (size_t)b * c->C, c->d_bias + (size_t)(b + 1) * c->C, tb[tcur], in_slots, rsum,
                                      tb[tcur ^ 1], is_last(b + 1), c->num_cu, buf[cur ^ 1], s);
                 if (e != hipSuccess) return hip_fail(c, e, "conv_pair launch");
+                time_end(t, s);
                 in_slots = conv_pair_records_per_image();
             } else {
+                qrm_ctx::Timed *t = time_begin(c, may_time, is_last(b) ? QRM_PROFILE_BLOCK_LAST : QRM_PROFILE_BLOCK_MID,
+                                               block_flops * cnt, s);
                 e = launch_conv_mid(base, buf_off[cur], g, c->C, c->d_w_mid[m], c->d_bias + (size_t)b * c->C, tb[tcur], in_slots,
                                     rsum, tb[tcur ^ 1], pm, is_last(b), buf[cur ^ 1], s);
                 if (e != hipSuccess) return hip_fail(c, e, "conv_mid launch");
+                time_end(t, s);
                 in_slots = pm.slots * pm.sub;
-            }
-            if (timed) {
-                (void)hipEventRecord(ev1, s);
-                c->prof_flops += (pair ? 2.0 : 1.0) * 2.0 * 9.0 * c->C * c->C * (double)h * w * cnt;
-                c->prof_blocks = pair ? 2 : 1;
             }
             cur ^= 1;
             tcur ^= 1;
@@ -445,6 +443,7 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
         float *lg = d_logits ? d_logits + n0 * c->n_bits : nullptr;
         uint8_t *bt = d_bits ? d_bits + n0 * c->n_bits : nullptr;
         uint8_t *sy = nsym ? d_symbols + n0 * nsym : nullptr;
+        qrm_ctx::Timed *t = time_begin(c, may_time, QRM_PROFILE_HEAD, 0.0, s);
         if (c->collapse) {
             e = launch_head(tb[tcur], in_slots, c->C, cnt, c->n_bits, c->nbp, inv_hw, c->d_wft, c->d_bias_final,
                             c->d_lin_w, c->d_lin_b, lg, bt, sy, m_sym > 0 ? m_sym : 1, s);
@@ -458,9 +457,14 @@ qrm_status run_extractor(qrm_ctx *c, Slot *slot, const WsLayout &L, TileSrc src,
                                    m_sym > 0 ? m_sym : 1, s);
             if (e != hipSuccess) return hip_fail(c, e, "linear_pack launch");
         }
+        time_end(t, s);
     }
     return QRM_OK;
 }
+
+} // namespace qrm
+
+namespace {
 
 bool build_gf_tables(int m, uint32_t poly, std::vector<uint8_t> &exp2, std::vector<uint8_t> &lg)
 {
@@ -482,48 +486,6 @@ bool build_gf_tables(int m, uint32_t poly, std::vector<uint8_t> &exp2, std::vect
 } // namespace
 
 extern "C" {
-
-qrm_status qrm_matrix_rate_probe(qrm_ctx *c, int32_t data, double *tflops)
-{
-    if (!c) return QRM_E_INVALID;
-    if (data < 0 || data > 2 || !tflops) return fail(c, QRM_E_INVALID, "data is 0 (zeros), 1 (a constant) or 2 (random); tflops must not be NULL");
-    hipError_t e = hipSetDevice(c->device);
-    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
-    // operands: A side like rounded weights (normal, small), B side like activations after a ReLU
-    std::vector<float> h(8192);
-    uint64_t state = 0x9E3779B97F4A7C15ull;
-    auto uni = [&]() {
-        state = state * 6364136223846793005ull + 1442695040888963407ull;
-        return ((double)(state >> 11) + 1.0) / 9007199254740994.0;
-    };
-    for (int i = 0; i < 8192; ++i) {
-        const double n = sqrt(-2.0 * log(uni())) * cos(6.283185307179586 * uni());
-        h[i] = data == 0 ? 0.f : data == 1 ? 1.5f : (float)(i >= 4096 ? (n > 0 ? n : 0.0) : 0.06 * n);
-    }
-    const int blocks = c->num_cu, iters = 8000, reps = 3;
-    float *d_src = nullptr, *d_out = nullptr;
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    e = hipMalloc(&d_src, h.size() * 4);
-    if (e == hipSuccess) e = hipMalloc(&d_out, (size_t)blocks * 512 * 4);
-    if (e == hipSuccess) e = hipMemcpy(d_src, h.data(), h.size() * 4, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipEventCreate(&e0);
-    if (e == hipSuccess) e = hipEventCreate(&e1);
-    if (e == hipSuccess) e = launch_matrix_rate(d_src, iters, blocks, d_out, nullptr); // warm-up
-    if (e == hipSuccess) e = hipEventRecord(e0, nullptr);
-    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch_matrix_rate(d_src, iters, blocks, d_out, nullptr);
-    if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    float ms = 0.f;
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
-    if (d_src) (void)hipFree(d_src);
-    if (d_out) (void)hipFree(d_out);
-    if (e != hipSuccess) return hip_fail(c, e, "matrix rate probe");
-    const double flops = (double)reps * blocks * 8 * (double)iters * 4 * 32768.0; // 2 * 32 * 32 * 16 per instruction
-    *tflops = flops / ((double)ms * 1e-3) / 1e12;
-    return QRM_OK;
-}
 
 const char *qrm_version(void) { return "qrm 0.1 gfx950"; }
 
@@ -656,7 +618,8 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
             delete c;
             return hip_fail(nullptr, e, "hipMemcpy(tables)");
         }
-        c->rs = RsParams{rs->m, q, rs->n, rs->k, rs->n - rs->k, rs->fcr, (const uint8_t *)c->d_tables,
+        // alpha has order q - 1: only fcr mod (q - 1) matters, and the kernels multiply it by positions in 32 bits
+        c->rs = RsParams{rs->m, q, rs->n, rs->k, rs->n - rs->k, rs->fcr % (q - 1), (const uint8_t *)c->d_tables,
                          (const uint8_t *)c->d_tables + 512};
     }
     *out = c;
@@ -667,12 +630,18 @@ void qrm_destroy(qrm_ctx *c)
 {
     if (!c) return;
     (void)hipSetDevice(c->device);
-    for (auto &sl : c->slots)
-        if (sl.used) {
-            (void)hipStreamSynchronize(sl.stream);
-            if (sl.ws) (void)hipFree(sl.ws);
+    for (auto &sl : c->slots) {
+        // the caller's stream may be gone by now: the event behind the workspace's last call is what is waited for
+        if (sl.done) {
+            if (sl.last_use) (void)hipEventSynchronize(sl.done);
+            (void)hipEventDestroy(sl.done);
         }
-    for (auto ev : c->ev_pool) (void)hipEventDestroy(ev);
+        if (sl.ws) (void)hipFree(sl.ws);
+    }
+    for (auto &t : c->timed) {
+        (void)hipEventDestroy(t.start);
+        (void)hipEventDestroy(t.stop);
+    }
     for (hipStream_t s : {c->s_up, c->s_run, c->s_down})
         if (s) (void)hipStreamSynchronize(s);
     for (auto &sg : c->stages) {
@@ -689,32 +658,52 @@ void qrm_destroy(qrm_ctx *c)
     delete c;
 }
 
+qrm_status qrm_release_stream(qrm_ctx *c, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
+    for (auto &sl : c->slots)
+        if (sl.used && sl.stream == (hipStream_t)stream) {
+            if (sl.done && sl.last_use) {
+                e = hipEventSynchronize(sl.done);
+                if (e != hipSuccess) return hip_fail(c, e, "hipEventSynchronize");
+            }
+            sl.used = false;
+            sl.stream = nullptr;
+            sl.last_use = 0; // idle: the next stream takes it without waiting
+        }
+    return QRM_OK;
+}
+
 qrm_status qrm_profile_enable(qrm_ctx *c, int32_t on)
 {
     if (!c) return QRM_E_INVALID;
     c->profile = on != 0;
-    c->ev_used = 0;
-    c->prof_flops = 0.0;
+    c->timed_used = 0;
     return QRM_OK;
 }
 
-qrm_status qrm_profile_read(qrm_ctx *c, double *ms_total, int64_t *launches, double *flops, int32_t *blocks_per_launch)
+qrm_status qrm_profile_read(qrm_ctx *c, int32_t kind, double *ms_total, int64_t *launches, double *flops)
 {
     if (!c) return QRM_E_INVALID;
-    double ms = 0.0;
-    for (size_t i = 0; i + 1 < c->ev_used; i += 2) {
-        hipError_t e = hipEventSynchronize(c->ev_pool[i + 1]);
-        float t = 0.f;
-        if (e == hipSuccess) e = hipEventElapsedTime(&t, c->ev_pool[i], c->ev_pool[i + 1]);
+    if (kind < 0 || kind >= QRM_PROFILE_KINDS) return fail(c, QRM_E_INVALID, "kind is one of the QRM_PROFILE_* values");
+    double ms = 0.0, fl = 0.0;
+    int64_t cnt = 0;
+    for (size_t i = 0; i < c->timed_used; ++i) {
+        const qrm_ctx::Timed &t = c->timed[i];
+        if (t.kind != kind) continue;
+        hipError_t e = hipEventSynchronize(t.stop);
+        float dt = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&dt, t.start, t.stop);
         if (e != hipSuccess) return hip_fail(c, e, "hipEventElapsedTime");
-        ms += t;
+        ms += dt;
+        fl += t.flops;
+        ++cnt;
     }
     if (ms_total) *ms_total = ms;
-    if (launches) *launches = (int64_t)(c->ev_used / 2);
-    if (flops) *flops = c->prof_flops;
-    if (blocks_per_launch) *blocks_per_launch = c->prof_blocks;
-    c->ev_used = 0;
-    c->prof_flops = 0.0;
+    if (launches) *launches = cnt;
+    if (flops) *flops = fl;
     return QRM_OK;
 }
 
@@ -801,12 +790,15 @@ static qrm_status extractor_common(qrm_ctx *c, const uint8_t *d_tiles, int64_t N
     if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
     hipStream_t s = (hipStream_t)stream;
     WsLayout L = ws_layout(c, N, h, w, false);
-    Slot *slot = nullptr;
+    if (L.mb < 1) return fail(c, QRM_E_UNSUPPORTED, "the activations of one tile exceed 1900 MiB");
+    QrmSlot *slot = nullptr;
     qrm_status st = get_slot(c, s, L.total, &slot);
     if (st != QRM_OK) return st;
     TileSrc src{d_tiles, nullptr, h, w, {c->mean[0], c->mean[1], c->mean[2]},
                 {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
-    return run_extractor(c, slot, L, src, N, h, w, n_run, d_logits, d_bits, nullptr, 0, d_act, s);
+    st = run_extractor(c, (uint8_t *)slot->ws, L, src, N, h, w, n_run, d_logits, d_bits, nullptr, 0, d_act, true, s);
+    const qrm_status st2 = slot_done(c, slot, s); // also after an error: kernels may have been enqueued
+    return st != QRM_OK ? st : st2;
 }
 
 qrm_status qrm_extractor_forward(qrm_ctx *c, const uint8_t *d_tiles, int64_t N, int32_t h, int32_t w,
@@ -901,12 +893,11 @@ qrm_status qrm_verify_key(qrm_ctx *c, const uint8_t *d_msg, int64_t N, int32_t *
 
 } // extern "C"
 
-static qrm_status detect_common(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
-                                const int32_t *d_off_yx, int32_t tile, float *d_logits, uint8_t *d_bits,
-                                uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, bool verify, int32_t *d_matches,
-                                uint8_t *d_detected, void *stream)
+namespace qrm {
+
+qrm_status check_detect_args(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W, int32_t tile,
+                             uint8_t *d_msg, int8_t *d_nerr, bool verify, int32_t *d_matches)
 {
-    if (!c) return QRM_E_INVALID;
     if (!c->has_ext || !c->has_rs) return fail(c, QRM_E_INVALID, "context needs both an extractor and a code");
     if (verify && !c->has_key) return fail(c, QRM_E_INVALID, "context has no key (qrm_set_key)");
     if (verify && N > 0 && !d_matches) return fail(c, QRM_E_INVALID, "d_matches is NULL");
@@ -914,25 +905,43 @@ static qrm_status detect_common(qrm_ctx *c, const uint8_t *d_images, int64_t N, 
     if (N < 0) return fail(c, QRM_E_INVALID, "N < 0");
     if (tile <= 0 || H <= 0 || W <= 0 || tile > H || tile > W || H > 16384 || W > 16384)
         return fail(c, QRM_E_INVALID, "need 0 < tile <= H, W <= 16384");
+    if (N > 0 && (!d_images || !d_msg || !d_nerr)) return fail(c, QRM_E_INVALID, "d_images / d_msg / d_nerr is NULL");
+    return QRM_OK;
+}
+
+} // namespace qrm
+
+static qrm_status detect_common(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                                const int32_t *d_off_yx, int32_t tile, float *d_logits, uint8_t *d_bits,
+                                uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, bool verify, int32_t *d_matches,
+                                uint8_t *d_detected, void *stream)
+{
+    if (!c) return QRM_E_INVALID;
+    qrm_status st = check_detect_args(c, d_images, N, H, W, tile, d_msg, d_nerr, verify, d_matches);
+    if (st != QRM_OK) return st;
     if (N == 0) return QRM_OK;
-    if (!d_images || !d_msg || !d_nerr) return fail(c, QRM_E_INVALID, "d_images / d_msg / d_nerr is NULL");
     hipError_t e = hipSetDevice(c->device);
     if (e != hipSuccess) return hip_fail(c, e, "hipSetDevice");
     hipStream_t s = (hipStream_t)stream;
     WsLayout L = ws_layout(c, N, tile, tile, true);
-    Slot *slot = nullptr;
-    qrm_status st = get_slot(c, s, L.total, &slot);
+    if (L.mb < 1) return fail(c, QRM_E_UNSUPPORTED, "the activations of one tile exceed 1900 MiB");
+    QrmSlot *slot = nullptr;
+    st = get_slot(c, s, L.total, &slot);
     if (st != QRM_OK) return st;
-    uint8_t *d_sym = (uint8_t *)slot->ws + kZeroBytes + 2 * L.act + L.partial + 2 * L.stats;
+    uint8_t *d_sym = (uint8_t *)slot->ws + symbols_offset(L);
     TileSrc src{d_images, d_off_yx, H, W, {c->mean[0], c->mean[1], c->mean[2]},
                 {c->inv_std[0], c->inv_std[1], c->inv_std[2]}};
-    st = run_extractor(c, slot, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, s);
-    if (st != QRM_OK) return st;
-    KeyArgs key{};
-    if (verify) key = KeyArgs{(const uint8_t *)c->d_tables + 768, c->key_tau, d_matches, d_detected};
-    e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, key, s);
-    if (e != hipSuccess) return hip_fail(c, e, "rs_decode launch");
-    return QRM_OK;
+    st = run_extractor(c, (uint8_t *)slot->ws, L, src, N, tile, tile, -1, d_logits, d_bits, d_sym, c->rs.m, nullptr, true, s);
+    if (st == QRM_OK) {
+        KeyArgs key{};
+        if (verify) key = KeyArgs{(const uint8_t *)c->d_tables + 768, c->key_tau, d_matches, d_detected};
+        qrm_ctx::Timed *t = time_begin(c, true, QRM_PROFILE_RS_DECODE, 0.0, s);
+        e = launch_rs_decode(c->rs, d_sym, N, d_msg, d_codeword, d_nerr, key, s);
+        if (e != hipSuccess) st = hip_fail(c, e, "rs_decode launch");
+        time_end(t, s);
+    }
+    const qrm_status st2 = slot_done(c, slot, s); // also after an error: kernels may have been enqueued
+    return st != QRM_OK ? st : st2;
 }
 
 extern "C" {
@@ -1055,12 +1064,17 @@ qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n
         e = hipEventRecord(sg.computed, c->s_run);
         if (e != hipSuccess) { st = hip_fail(c, e, "hipEventRecord"); break; }
         submitted = i + 1;
-        if (i >= 1) {
-            e = download(i - 1);
+        // The download of a chunk must be submitted before the kernels of the next chunk that shares its
+        // staging buffer (their wait on `downloaded` above refers to the event as recorded by then).  With
+        // two or more buffers that is the chunk before this one, submitted behind this chunk's upload; with
+        // a single buffer it is this chunk itself.
+        const int due = used == 1 ? i : i - 1;
+        if (due >= 0) {
+            e = download(due);
             if (e != hipSuccess) st = hip_fail(c, e, "download of a chunk");
         }
     }
-    if (st == QRM_OK && submitted >= 1) {
+    if (st == QRM_OK && submitted >= 1 && used > 1) {
         e = download(submitted - 1);
         if (e != hipSuccess) st = hip_fail(c, e, "download of a chunk");
     }

@@ -134,9 +134,6 @@ bool preprocess_supported(int H_in, int W_in, int x, int T);
 hipError_t launch_preprocess(const uint8_t *raw, int64_t N, int H_in, int W_in, int x, const int32_t *off, int T,
                              uint8_t *out, hipStream_t s);
 
-// Diagnostic: back-to-back matrix instructions on operands made from src (device, 8192 floats); out: blocks*512 floats.
-hipError_t launch_matrix_rate(const float *src, int iters, int blocks, float *out, hipStream_t s);
-
 // host-side helpers
 uint16_t f32_to_bf16_rne(float f);
 

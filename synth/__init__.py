@@ -23,7 +23,7 @@ import numpy as np
 BASE_SEED = 250902447
 
 # purpose tags
-_T_IMAGE, _T_OFFSET, _T_WEIGHT, _T_RS = 1, 2, 3, 4
+_T_IMAGE, _T_OFFSET, _T_WEIGHT, _T_RS, _T_FIELD = 1, 2, 3, 4, 5
 
 MEAN = (0.485, 0.456, 0.406)
 STD = (0.229, 0.224, 0.225)
@@ -77,16 +77,55 @@ def _rng(cfg_index: int, tag: int, block: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(ss))
 
 
-def images(cfg: Config, start: int, count: int, out: np.ndarray | None = None) -> np.ndarray:
-    """uint8 [count,3,H,W], uniform 0..255; image i depends only on (cfg.index, i)."""
+def images(cfg: Config, start: int, count: int, out: np.ndarray | None = None, threads: int = 1) -> np.ndarray:
+    """uint8 [count,3,H,W], uniform 0..255; image i depends only on (cfg.index, i).  threads > 1 fills disjoint
+    runs of images from that many host threads (same bytes: every image has its own generator)."""
     per = 3 * cfg.H * cfg.W
     if out is None:
         out = np.empty((count, 3, cfg.H, cfg.W), dtype=np.uint8)
     flat = out.reshape(count, per)
-    for j in range(count):
-        g = _rng(cfg.index, _T_IMAGE, start + j)
-        flat[j] = np.frombuffer(g.bytes(per), dtype=np.uint8)
+
+    def fill(lo: int, hi: int) -> None:
+        for j in range(lo, hi):
+            g = _rng(cfg.index, _T_IMAGE, start + j)
+            flat[j] = np.frombuffer(g.bytes(per), dtype=np.uint8)
+
+    if threads <= 1 or count < 2 * threads:
+        fill(0, count)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        step = (count + threads - 1) // threads
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(lambda t: fill(t * step, min(count, (t + 1) * step)), range(threads)))
     return out
+
+
+def field_images(cfg: Config, start: int, count: int) -> np.ndarray:
+    """uint8 [count,3,H,W] images that differ from one another in the large: per image and channel a random
+    level, a random linear ramp across the image, and uniform noise of a random amplitude (0 = a smooth image),
+    clipped to 0..255.  Unlike i.i.d. noise, whose pooled features are the same for every image, these give
+    every image its own soft bits; image i depends only on (cfg.index, i).  About a twelfth of the images are
+    flat instead (field_is_flat): black, white, or one level per channel."""
+    out = np.empty((count, 3, cfg.H, cfg.W), dtype=np.uint8)
+    yy, xx = np.meshgrid(np.arange(cfg.H, dtype=np.float64), np.arange(cfg.W, dtype=np.float64), indexing="ij")
+    for j in range(count):
+        g = _rng(cfg.index, _T_FIELD, start + j)
+        flat = int(g.integers(0, 12)) == 0
+        level = g.uniform(0.0, 255.0, size=3)
+        ramp = g.uniform(-160.0, 160.0, size=(3, 2))        # grey levels across the whole height / width
+        amp = g.choice([0.0, 8.0, 48.0, 128.0])
+        noise = g.uniform(-1.0, 1.0, size=(3, cfg.H, cfg.W))
+        for c in range(3):
+            v = level[c] + ramp[c, 0] * (yy / cfg.H - 0.5) + ramp[c, 1] * (xx / cfg.W - 0.5) + amp * noise[c]
+            if flat:
+                v = np.full_like(v, (0.0, 255.0, level[c])[(start + j) % 3])
+            out[j, c] = np.clip(np.rint(v), 0, 255).astype(np.uint8)
+    return out
+
+
+def field_is_flat(cfg: Config, start: int, count: int) -> np.ndarray:
+    """bool [count]: which images of field_images(cfg, start, count) are flat."""
+    return np.array([int(_rng(cfg.index, _T_FIELD, start + j).integers(0, 12)) == 0 for j in range(count)], dtype=bool)
 
 
 def offsets(cfg: Config, start: int, count: int, policy: str = "random") -> np.ndarray:

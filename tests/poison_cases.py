@@ -1,9 +1,8 @@
-"""Detection on a few small batches of every configuration shape; run as a script it writes the logits to a file.
+"""Detection on a few small batches of every configuration shape, under a set of the library's diagnostic flags.
 
-Used by the GPU test that runs this file in a child process under one of the library's environment switches -
-QRM_POISON_WORKSPACE=1 (every new workspace is filled with 0xFF bytes, NaN as bf16 and as fp32: a kernel that
-reads workspace bytes which no kernel wrote would show up as a difference, or as NaN) or QRM_DISABLE_PAIRS=1 (one
-launch per block) - and compares with the same calls in the parent.
+Used by the GPU test that compares a plain run with a run under QRM_DIAG_POISON_WORKSPACE (every new workspace is
+filled with 0xFF bytes, NaN as bf16 and as fp32: a kernel that reads workspace bytes which no kernel wrote would
+show up as a difference, or as NaN) or QRM_DIAG_NO_FUSED_PAIRS (one launch per block).
 """
 import os
 import sys
@@ -17,7 +16,7 @@ if ROOT not in sys.path:
 CASES = [("C1", 16, 0), ("C2", 40, 16), ("C2", 7, 0), ("C4", 5, 2), ("C3", 2, 1)]   # configuration, images, micro-batch
 
 
-def run_cases():
+def run_cases(diag_flags=0):
     import torch
     import synth
     import paper_2509_02447_amd as q
@@ -27,6 +26,7 @@ def run_cases():
         cfg = synth.CONFIGS[name]
         ctx = q.Context(weights=synth.config_weights(cfg),
                         rs=dict(m=cfg.m, prim_poly=cfg.prim_poly, n=cfg.n, k=cfg.k, fcr=cfg.fcr))
+        ctx.qrm_diag_set_flags(diag_flags)
         if mb:
             ctx.qrm_set_micro_batch(mb)
         imgs = torch.from_numpy(synth.images(cfg, 7, N)).cuda()
@@ -41,8 +41,3 @@ def run_cases():
             out[f"{name}_{N}_{rep}_msg"] = msg.cpu().numpy()
         ctx.close()
     return out
-
-
-if __name__ == "__main__":
-    np.savez(sys.argv[1], **run_cases())
-    print("wrote", sys.argv[1], flush=True)

@@ -6,8 +6,8 @@ import re
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "qrm.h")).read()
+def declared_symbols(header="qrm.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     return re.findall(r"QRM_API\s+[\w\s\*]+?\b(qrm_\w+)\s*\(", text)
 
 
@@ -26,6 +26,9 @@ def test_library_exports_every_declared_symbol():
     for name in declared_symbols():
         assert hasattr(lib, name), name
     assert set(declared_symbols()) == set(binding.EXPORTS)
+    for name in declared_symbols("qrm_diag.h"):
+        assert hasattr(lib, name), name
+    assert set(declared_symbols("qrm_diag.h")) == set(binding.DIAG_EXPORTS)
     lib.qrm_version.restype = ctypes.c_char_p
     assert b"gfx950" in lib.qrm_version()
 

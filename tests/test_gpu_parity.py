@@ -373,24 +373,78 @@ def test_detect_config_c2_full_size_sampled(qrm):
     check_logits(got["logits"][sample], ref["logits"], got["bits"][sample], what=f"C2 full size, {len(sample)} sampled images")
 
 
-def test_detect_config_c4_sample(qrm):
+HOST_THREADS = min(16, os.cpu_count() or 1)
+
+
+def sampled_config_parity(qrm, name, N, sample, what, micro_batch=0):
+    """qrm_detect over N images of a configuration in its default launch configuration; the images in `sample`
+    against the oracle one by one (logits, hard bits), the Reed-Solomon outputs of ALL images against the oracle's
+    decoder on the device's own hard bits, and bits = (logit > 0) everywhere."""
+    cfg = synth.CONFIGS[name]
+    wts = synth.config_weights(cfg)
+    imgs = synth.images(cfg, 0, N, threads=HOST_THREADS)
+    off = synth.offsets(cfg, 0, N)
+    # a few images that differ in the large (ramps, flat levels) instead of noise, on both sides of the first
+    # micro-batch boundaries: their bits and error counts differ from image to image
+    special = [i for i in sample if i % 3 == 1]
+    fld = synth.field_images(cfg, 0, len(special))
+    flat = synth.field_is_flat(cfg, 0, len(special))
+    for j, i in enumerate(special):
+        imgs[i] = fld[j]
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    if micro_batch:
+        ctx.qrm_set_micro_batch(micro_batch)
+    got = run_detect(ctx, cfg, imgs, off)
+    ctx.close()
+    assert np.isfinite(got["logits"]).all()
+    assert np.array_equal(got["bits"], (got["logits"] > 0).astype(np.uint8))
+    syms = oracle.bits_to_symbols(got["bits"], cfg.m)
+    om, oc, oe = oracle.rs_decode(syms, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    assert np.array_equal(got["msg"], om) and np.array_equal(got["codeword"], oc) and np.array_equal(got["nerr"], oe)
+    ref = oracle.detect(wts, imgs[sample], off[sample], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    is_flat = np.array([i in special and bool(flat[special.index(i)]) for i in sample])
+    check_logits(got["logits"][sample], ref["logits"], got["bits"][sample], what=what, flat=is_flat)
+    same = np.all(got["bits"][sample] == ref["bits"], axis=1)
+    assert np.array_equal(got["msg"][sample][same], ref["msg"][same]) and np.array_equal(got["nerr"][sample][same], ref["nerr"][same])
+    print(f"[parity] {what}: {int(same.sum())} of {len(sample)} sampled images have every hard bit equal to the oracle's; "
+          f"{len(special)} structured images ({int(flat.sum())} flat); distinct messages in the sample: "
+          f"{len({tuple(r) for r in got['msg'][sample]})}")
+    return got
+
+
+@pytest.mark.timeout(600)
+def test_detect_config_c4_full_micro_batches_sampled(qrm):
+    """128 x 128 tiles of 512 x 512 images with byte symbols: 1030 images = several default micro-batches and a
+    ragged one; 64 images against the oracle (both sides of every multiple of 256 images, the first and the last
+    image, a random draw), every Reed-Solomon output against the oracle's decoder."""
+    N = 1030
+    rng = np.random.default_rng(4)
+    sample = sorted(set([0, 1, 255, 256, 257, 511, 512, 513, 767, 768, 1023, 1024, 1025, N - 2, N - 1] +
+                        rng.integers(0, N, size=52).tolist()))[:64]
+    sampled_config_parity(qrm, "C4", N, sample, f"C4 detect, {N} images, {len(sample)} sampled")
+
+
+@pytest.mark.timeout(600)
+def test_detect_config_c3_full_micro_batches_sampled(qrm):
+    """Untiled 256 x 256 detection: 515 images = several default micro-batches (64 or 256 images) and a ragged
+    one; 48 images against the oracle, every Reed-Solomon output against the oracle's decoder."""
+    N = 515
+    rng = np.random.default_rng(3)
+    sample = sorted(set([0, 1, 63, 64, 65, 127, 128, 255, 256, 257, 511, 512, 513, N - 1] +
+                        rng.integers(0, N, size=40).tolist()))[:48]
+    sampled_config_parity(qrm, "C3", N, sample, f"C3 detect (untiled 256x256), {N} images, {len(sample)} sampled")
+
+
+def test_detect_config_c4_small_micro_batches(qrm):
+    """The same configuration with a micro-batch of 3: many launches, a workgroup sees parts of images only."""
     cfg = synth.CONFIGS["C4"]
     wts = synth.config_weights(cfg)
-    N = 3
+    N = 7
     imgs, off = synth.images(cfg, 7, N), synth.offsets(cfg, 7, N)
     ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    ctx.qrm_set_micro_batch(3)
     got = run_detect(ctx, cfg, imgs, off)
-    check_detect(cfg, wts, imgs, off, got, f"C4 detect, {N} images")
-    ctx.close()
-
-
-def test_detect_config_c3_one_image(qrm):
-    cfg = synth.CONFIGS["C3"]
-    wts = synth.config_weights(cfg)
-    imgs = synth.images(cfg, 3, 1)
-    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
-    got = run_detect(ctx, cfg, imgs, None)
-    check_detect(cfg, wts, imgs, None, got, "C3 detect (untiled 256x256), 1 image")
+    check_detect(cfg, wts, imgs, off, got, f"C4 detect, {N} images, micro-batch 3")
     ctx.close()
 
 
@@ -414,35 +468,87 @@ def test_detect_equals_separate_calls(qrm):
     ctx.close()
 
 
-@pytest.mark.parametrize("switch,tol", [("QRM_POISON_WORKSPACE", 5e-4), ("QRM_DISABLE_PAIRS", 2 * 2e-2)])
-def test_library_switches_do_not_change_results(qrm, tmp_path, switch, tol):
-    """The library's two environment switches, each in a child process against this process's plain run.
-    Poisoned workspaces (every new one filled with 0xFF bytes, NaN as bf16 and as fp32): no kernel reads workspace
-    bytes that no kernel wrote, so the results agree up to the order of atomic additions.  Unfused blocks (one
-    launch per block): another schedule and other roundings of the same layers, so the two results, each within
-    the tolerance of the exact one, lie within twice that of each other."""
-    import subprocess
-    import sys
+@pytest.mark.parametrize("flag,tol", [("QRM_DIAG_POISON_WORKSPACE", 0.0), ("QRM_DIAG_NO_FUSED_PAIRS", 2 * 2e-2)])
+def test_diagnostic_flags_do_not_change_results(qrm, flag, tol):
+    """The library's two diagnostic flags against the plain run.  Poisoned workspaces (every new one filled with
+    0xFF bytes, NaN as bf16 and as fp32): no kernel reads workspace bytes that no kernel wrote, and sums are formed
+    in a fixed order, so the results are the same bit for bit.  Unfused blocks (one launch per block): another
+    schedule and other roundings of the same layers, so the two results, each within the tolerance of the exact
+    one, lie within twice that of each other."""
     import poison_cases
-    mine = poison_cases.run_cases()
-    path = str(tmp_path / "poisoned.npz")
-    env = dict(os.environ, **{switch: "1"})
-    r = subprocess.run([sys.executable, os.path.join(os.path.dirname(__file__), "poison_cases.py"), path], env=env,
-                       capture_output=True, text=True, timeout=110)
-    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
-    theirs = np.load(path)
-    assert sorted(theirs.files) == sorted(mine)
+    mine = poison_cases.run_cases(0)
+    theirs = poison_cases.run_cases(getattr(qrm.binding, flag))
+    assert sorted(theirs) == sorted(mine)
     for key, a in mine.items():
         b = theirs[key]
         assert np.isfinite(b).all(), key
-        if key.endswith("logits"):   # sums over LDS atomics: the order of the additions is not fixed
-            twin = mine[key.replace("_0_logits", "_1_logits").replace("_1_logits", "_0_logits") if "_0_" in key
-                        else key.replace("_1_logits", "_0_logits")]
-            print(f"[{switch}] {key}: max |child - plain| {float(np.abs(a - b).max()):.2e}, "
-                  f"between two plain calls {float(np.abs(a - twin).max()):.2e}")
-            assert (np.abs(a - b) <= tol * np.maximum(1.0, np.abs(a))).all(), (key, float(np.abs(a - b).max()))
-        elif switch == "QRM_POISON_WORKSPACE":
+        if tol == 0.0:
             assert np.array_equal(a, b), key
+        elif key.endswith("logits"):
+            print(f"[{flag}] {key}: max |flagged - plain| {float(np.abs(a - b).max()):.2e}")
+            assert (np.abs(a - b) <= tol * np.maximum(1.0, np.abs(a))).all(), (key, float(np.abs(a - b).max()))
+
+
+def test_results_are_reproducible_bit_for_bit(qrm):
+    """Two calls give the same bytes: every sum inside the kernels is formed in a fixed order.  On the fused path
+    (64 channels) that order depends on the image alone, so other splits of the batch into micro-batches give the
+    same bytes too; on the single-block path (32 channels) a split deals an image's strips to other workgroups, and
+    the last fp32 bits of the channel sums may then differ."""
+    for name, N, mbs in (("C2", 1300, (0, 300, 1024)), ("C1", 300, (0, 7))):
+        cfg = synth.CONFIGS[name]
+        imgs = synth.images(cfg, 0, N, threads=HOST_THREADS)
+        fld = synth.field_images(cfg, 100, 40)
+        imgs[::N // 40][:40] = fld
+        off = synth.offsets(cfg, 0, N)
+        ctx = qrm.Context(weights=synth.config_weights(cfg), rs=rs_dict(cfg))
+        runs = []
+        for mb in mbs + (mbs[0],):
+            ctx.qrm_set_micro_batch(mb)
+            runs.append(run_detect(ctx, cfg, imgs, off))
+        ctx.close()
+        for r, mb in zip(runs[1:], (mbs + (mbs[0],))[1:]):
+            exact = name == "C2" or mb == mbs[0]   # single-block path: other splits deal the strips to other workgroups
+            for key in ("logits", "bits", "msg", "codeword", "nerr"):
+                if exact:
+                    assert np.array_equal(runs[0][key], r[key]), (name, key, mb)
+            assert np.allclose(runs[0]["logits"], r["logits"], rtol=0, atol=2e-5), (name, mb)
+
+
+def test_more_streams_than_workspaces(qrm):
+    """Twenty short-lived streams, one after the other, on one context (which holds QRM_MAX_STREAMS = 8 workspaces):
+    a stream not seen before takes over the workspace used least recently.  Half of the streams are handed back
+    with qrm_release_stream before they are destroyed, half are just dropped."""
+    cfg = synth.CONFIGS["C2"]
+    N = 6
+    imgs, off = synth.images(cfg, 40, N), synth.offsets(cfg, 40, N)
+    ctx = qrm.Context(weights=synth.config_weights(cfg), rs=rs_dict(cfg))
+    base = run_detect(ctx, cfg, imgs, off)
+    d_img, d_off = dev(imgs), dev(off)
+    torch.cuda.synchronize()
+    for i in range(20):
+        s = torch.cuda.Stream()
+        d_logits = empty((N, cfg.n_bits), torch.float32)
+        d_msg, d_ne = empty((N, cfg.k), torch.uint8), empty((N,), torch.int8)
+        ctx.qrm_detect(d_img, N, cfg.H, cfg.W, d_off, cfg.tile, d_logits, None, d_msg, None, d_ne, stream=s)
+        if i % 2:
+            ctx.qrm_release_stream(s)
+        s.synchronize()
+        assert np.array_equal(d_logits.cpu().numpy(), base["logits"]), i
+        assert np.array_equal(d_msg.cpu().numpy(), base["msg"]) and np.array_equal(d_ne.cpu().numpy(), base["nerr"])
+        del s
+    # nine streams alive at once: the ninth shares a workspace with the first, in order
+    streams = [torch.cuda.Stream() for _ in range(9)]
+    outs = []
+    for s in streams:
+        d_logits = empty((N, cfg.n_bits), torch.float32)
+        d_msg, d_ne = empty((N, cfg.k), torch.uint8), empty((N,), torch.int8)
+        ctx.qrm_detect(d_img, N, cfg.H, cfg.W, d_off, cfg.tile, d_logits, None, d_msg, None, d_ne, stream=s)
+        outs.append((d_logits, d_msg, d_ne))
+    torch.cuda.synchronize()
+    for d_logits, d_msg, d_ne in outs:
+        assert np.array_equal(d_logits.cpu().numpy(), base["logits"]) and np.array_equal(d_msg.cpu().numpy(), base["msg"])
+    ctx.qrm_release_stream(torch.cuda.Stream())          # a stream the context never saw: no-op
+    ctx.close()
 
 
 def test_detect_on_two_streams(qrm):
@@ -471,13 +577,19 @@ def test_detect_on_two_streams(qrm):
 
 
 def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
-    """Images in pinned host chunks, streamed through 3 lanes with two of the buffers reused, give exactly
-    what qrm_detect gives on the same images resident in device memory (which the tests above check
-    against the oracle); spot check of the first chunk against the oracle itself."""
+    """Images in pinned host chunks streamed through 1, 2 and 3 staging buffers, with two of the host buffers
+    appearing twice, give what qrm_detect gives on the same images resident in device memory - chunk by chunk,
+    with chunks whose results differ (structured images: other bits, other error counts), so that a stale,
+    swapped or overwritten chunk shows.  The resident results are held against the oracle unconditionally:
+    logits and hard bits of a sample, every Reed-Solomon output against the oracle's decoder on the device's bits."""
     cfg = synth.CONFIGS["C2"]
     wts = synth.config_weights(cfg)
-    chunk, order = 40, [0, 1, 2, 0, 1]               # chunk pointers: buffers 0 and 1 appear twice
-    imgs = synth.images(cfg, 500, 3 * chunk)
+    chunk, order = 1100, [0, 1, 2, 0, 1]             # more images per chunk than one micro-batch; buffers 0, 1 twice
+    imgs = synth.images(cfg, 500, 3 * chunk, threads=HOST_THREADS)
+    fld = synth.field_images(cfg, 500, 3 * 48)
+    for b in range(3):                               # 48 structured images at the head and the tail of every chunk
+        imgs[b * chunk:b * chunk + 24] = fld[b * 48:b * 48 + 24]
+        imgs[(b + 1) * chunk - 24:(b + 1) * chunk] = fld[b * 48 + 24:(b + 1) * 48]
     off = synth.offsets(cfg, 500, 3 * chunk)
     bufs = [torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, pin_memory=True) for _ in range(3)]
     obufs = [torch.empty((chunk, 2), dtype=torch.int32, pin_memory=True) for _ in range(3)]
@@ -485,33 +597,101 @@ def test_detect_host_chunked_pipeline_equals_resident_detect(qrm):
         bufs[b].copy_(torch.from_numpy(imgs[b * chunk:(b + 1) * chunk]))
         obufs[b].copy_(torch.from_numpy(off[b * chunk:(b + 1) * chunk]))
     n_total = len(order) * chunk
-    h_msg = torch.empty((n_total, cfg.k), dtype=torch.uint8, pin_memory=True)
-    h_cw = torch.empty((n_total, cfg.n), dtype=torch.uint8, pin_memory=True)
-    h_ne = torch.empty((n_total,), dtype=torch.int8, pin_memory=True)
     ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
-    ctx.qrm_detect_host([bufs[b] for b in order], chunk, cfg.H, cfg.W, [obufs[b] for b in order], cfg.tile, 3,
-                        h_msg, h_cw, h_ne)
     base = run_detect(ctx, cfg, imgs, off)
-    for i, b in enumerate(order):
-        sl, bl = slice(i * chunk, (i + 1) * chunk), slice(b * chunk, (b + 1) * chunk)
-        assert np.array_equal(h_msg[sl].numpy(), base["msg"][bl])
-        assert np.array_equal(h_cw[sl].numpy(), base["codeword"][bl])
-        assert np.array_equal(h_ne[sl].numpy(), base["nerr"][bl])
-    # a second call on the same context (lanes and staging reused), one stream, no origins, no code words
+    # the resident results against the oracle
+    syms = oracle.bits_to_symbols(base["bits"], cfg.m)
+    om, oc, oe = oracle.rs_decode(syms, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    assert np.array_equal(base["msg"], om) and np.array_equal(base["codeword"], oc) and np.array_equal(base["nerr"], oe)
+    fflat = synth.field_is_flat(cfg, 500, 3 * 48)
+    sample, is_flat = [], []
+    for b in range(3):
+        for j in (0, 1, 2, 3, 24, 600, chunk - 1):
+            sample.append(b * chunk + j)
+            fi = b * 48 + j if j < 24 else (b * 48 + 24 + j - (chunk - 24) if j >= chunk - 24 else -1)
+            is_flat.append(fi >= 0 and bool(fflat[fi]))
+    ref = oracle.detect(wts, imgs[sample], off[sample], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+    check_logits(base["logits"][sample], ref["logits"], base["bits"][sample], what=f"streamed chunks, {len(sample)} sampled images",
+                 flat=np.array(is_flat))
+    # the chunks must be told apart by their results
+    heads = [base["msg"][b * chunk:b * chunk + 24].tobytes() + base["nerr"][b * chunk:b * chunk + 24].tobytes() for b in range(3)]
+    assert len(set(heads)) == 3, "the chunks of this test must differ in their results"
+    for depth in (1, 2, 3):
+        h_msg = torch.zeros((n_total, cfg.k), dtype=torch.uint8, pin_memory=True)
+        h_cw = torch.zeros((n_total, cfg.n), dtype=torch.uint8, pin_memory=True)
+        h_ne = torch.zeros((n_total,), dtype=torch.int8, pin_memory=True)
+        ctx.qrm_detect_host([bufs[b] for b in order], chunk, cfg.H, cfg.W, [obufs[b] for b in order], cfg.tile, depth,
+                            h_msg, h_cw, h_ne)
+        for i, b in enumerate(order):
+            sl, bl = slice(i * chunk, (i + 1) * chunk), slice(b * chunk, (b + 1) * chunk)
+            assert np.array_equal(h_msg[sl].numpy(), base["msg"][bl]), (depth, i)
+            assert np.array_equal(h_cw[sl].numpy(), base["codeword"][bl]), (depth, i)
+            assert np.array_equal(h_ne[sl].numpy(), base["nerr"][bl]), (depth, i)
+    # a second kind of call on the same context (staging reused): one buffer, no origins, no code words
     h_msg2 = torch.empty((2 * chunk, cfg.k), dtype=torch.uint8, pin_memory=True)
     h_ne2 = torch.empty((2 * chunk,), dtype=torch.int8, pin_memory=True)
     ctx.qrm_detect_host([bufs[2], bufs[0]], chunk, cfg.H, cfg.W, None, cfg.tile, 1, h_msg2, None, h_ne2)
     base0 = run_detect(ctx, cfg, np.concatenate([imgs[2 * chunk:], imgs[:chunk]]), None)
     assert np.array_equal(h_msg2.numpy(), base0["msg"]) and np.array_equal(h_ne2.numpy(), base0["nerr"])
-    # oracle on a few images of the first chunk: RS outputs follow from the GPU's own hard bits
-    ns = 4
-    ref = oracle.detect(wts, imgs[:ns], off[:ns], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
-    if np.array_equal(base["bits"][:ns], ref["bits"]):
-        assert np.array_equal(h_msg[:ns].numpy(), ref["msg"]) and np.array_equal(h_ne[:ns].numpy(), ref["nerr"])
+    assert not np.array_equal(base0["msg"][:chunk], base0["msg"][chunk:])
     with pytest.raises(qrm.QrmError) as e:
-        ctx.qrm_detect_host([bufs[0]], chunk, cfg.H, cfg.W, None, cfg.tile, 0, h_msg, None, h_ne)
+        ctx.qrm_detect_host([bufs[0]], chunk, cfg.H, cfg.W, None, cfg.tile, 0, h_msg2, None, h_ne2)
     assert e.value.status == qrm.QRM_E_INVALID
-    ctx.qrm_detect_host([], chunk, cfg.H, cfg.W, None, cfg.tile, 2, h_msg, None, h_ne)   # zero chunks: no-op
+    ctx.qrm_detect_host([], chunk, cfg.H, cfg.W, None, cfg.tile, 2, h_msg2, None, h_ne2)   # zero chunks: no-op
+    ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_detect_host_full_streamed_configuration(qrm):
+    """The streamed configuration at its real size: 128 chunks of 8192 images (1 048 576 images, 206 GB over the
+    host link per pass) through qrm_detect_host with 3, 2 and 1 staging buffers.  Eight distinct pinned chunks are
+    recycled (chunk i is buffer i mod 8), each with 64 structured images at its head, so that every chunk has
+    results of its own.  Every one of the 1 048 576 outputs must equal the resident qrm_detect output of its
+    buffer, which in turn equals the oracle's decoder on the device's own hard bits; the first 64 images of the
+    first and of the last chunk are held against the oracle's extractor."""
+    cfg = synth.CONFIGS["C5"]
+    wts = synth.config_weights(cfg)
+    chunk, n_chunks, n_buf = cfg.chunk, cfg.n_images // cfg.chunk, 8
+    assert chunk == 8192 and n_chunks == 128
+    bufs = [torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, pin_memory=True) for _ in range(n_buf)]
+    obufs = [torch.empty((chunk, 2), dtype=torch.int32, pin_memory=True) for _ in range(n_buf)]
+    for b in range(n_buf):
+        print(f"[stream] generating chunk {b}", flush=True)
+        synth.images(cfg, b * chunk, chunk, out=bufs[b].numpy(), threads=HOST_THREADS)
+        bufs[b][:64].copy_(torch.from_numpy(synth.field_images(cfg, b * 64, 64)))
+        obufs[b].copy_(torch.from_numpy(synth.offsets(cfg, b * chunk, chunk)))
+    ctx = qrm.Context(weights=wts, rs=rs_dict(cfg))
+    base = []
+    for b in range(n_buf):
+        got = run_detect(ctx, cfg, bufs[b].numpy(), obufs[b].numpy())
+        syms = oracle.bits_to_symbols(got["bits"], cfg.m)
+        om, oc, oe = oracle.rs_decode(syms, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+        assert np.array_equal(got["msg"], om) and np.array_equal(got["codeword"], oc) and np.array_equal(got["nerr"], oe)
+        base.append(got)
+    assert len({g["msg"][:64].tobytes() for g in base}) == n_buf
+    for b in (0, (n_chunks - 1) % n_buf):            # the first and the last chunk of the pass
+        ref = oracle.detect(wts, bufs[b].numpy()[:64], obufs[b].numpy()[:64], cfg.tile, cfg.m, cfg.prim_poly, cfg.n, cfg.k, cfg.fcr)
+        check_logits(base[b]["logits"][:64], ref["logits"], base[b]["bits"][:64], what=f"streamed configuration, buffer {b}, first 64 images",
+                     flat=synth.field_is_flat(cfg, b * 64, 64))
+    n_total = n_chunks * chunk
+    order = [i % n_buf for i in range(n_chunks)]
+    first = None
+    for depth in (3, 2, 1):
+        h_msg = torch.zeros((n_total, cfg.k), dtype=torch.uint8, pin_memory=True)
+        h_cw = torch.zeros((n_total, cfg.n), dtype=torch.uint8, pin_memory=True)
+        h_ne = torch.zeros((n_total,), dtype=torch.int8, pin_memory=True)
+        print(f"[stream] pass with {depth} staging buffer(s)", flush=True)
+        ctx.qrm_detect_host([bufs[b] for b in order], chunk, cfg.H, cfg.W, [obufs[b] for b in order], cfg.tile, depth,
+                            h_msg, h_cw, h_ne)
+        m3, c3, e3 = (h_msg.numpy().reshape(n_chunks, chunk, cfg.k), h_cw.numpy().reshape(n_chunks, chunk, cfg.n),
+                      h_ne.numpy().reshape(n_chunks, chunk))
+        for i, b in enumerate(order):
+            assert np.array_equal(m3[i], base[b]["msg"]) and np.array_equal(c3[i], base[b]["codeword"]) and \
+                np.array_equal(e3[i], base[b]["nerr"]), (depth, i)
+        digest = (h_msg.numpy().tobytes(), h_ne.numpy().tobytes())
+        if first is None:
+            first = digest
+        assert digest == first
     ctx.close()
 
 
@@ -893,11 +1073,11 @@ def test_whole_chain_raw_image_to_verdict(qrm):
 def test_matrix_rate_probe_reports_plausible_rates(qrm):
     """The diagnostic probe: zeros run near the published rate, random operands slower, both far above zero."""
     ctx = qrm.Context(rs=rs_dict(synth.CONFIGS["C1"]))
-    zeros, rnd = ctx.qrm_matrix_rate_probe(0), ctx.qrm_matrix_rate_probe(2)
+    zeros, rnd = ctx.qrm_diag_matrix_rate(0), ctx.qrm_diag_matrix_rate(2)
     print(f"[probe] matrix pipes: {zeros:.0f} TFLOP/s on zeros, {rnd:.0f} TFLOP/s on random operands")
     assert 500.0 < rnd <= zeros * 1.05 and zeros < 2700.0
     with pytest.raises(qrm.QrmError):
-        ctx.qrm_matrix_rate_probe(3)
+        ctx.qrm_diag_matrix_rate(3)
     ctx.close()
 
 
