@@ -19,7 +19,7 @@ extern "C" {
                                        schedules round differently, both within the tolerance) */
 #define QRM_DIAG_POISON_WORKSPACE 2 /* fill every newly allocated workspace with 0xFF bytes (NaN as bf16 and as
                                        fp32): a kernel that reads workspace bytes no kernel wrote shows in the
-                                       results */
+                                       results; bits 8..15 of the flags, when not zero, give another fill byte */
 
 /* Sets the context's diagnostic flags (0 = production behaviour).  Affects calls made afterwards. */
 QRM_API qrm_status qrm_diag_set_flags(qrm_ctx *ctx, int32_t flags);

@@ -79,6 +79,10 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 // two fp32 -> packed bf16 (round to nearest even) with ReLU applied on the packed pair: a negative bf16
 // has its sign bit set, i.e. is negative as a 16-bit integer, so max(.,0) on the halves clamps it.
+// The operands must not be the result registers of a matrix instruction: the compiler puts the wait states a
+// matrix result needs in front of its own instructions only, not in front of an asm statement, which would
+// then now and then read the registers before the last matrix instruction has written them (seen as
+// run-to-run differences of one bf16 step).  Every caller adds the bias first.
 __device__ __forceinline__ uint32_t pack_bf16_relu(float a, float b, bool relu)
 {
     uint32_t p; // (the compiler would convert the two halves separately and merge them with a permute)
@@ -1344,11 +1348,16 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
                     const u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
                     bfrag[q] = __builtin_bit_cast(bf16x8, both);
                 }
-                f32x16 acc = bias16;
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                f32x16 sum = mfma32(Wr[0][0], bfrag[0], zero);
+                sum = mfma32(Wr[0][1], bfrag[1], sum);
+                sum = mfma32(Wr[0][2], bfrag[2], sum);
 #pragma unroll
-                for (int p = 0; p < 2; ++p)
+                for (int q = 0; q < 3; ++q) sum = mfma32(Wr[1][q], bfrag[q], sum);
+                // the bias is added by ordinary vector instructions: see pack_bf16_relu
+                f32x16 acc;
 #pragma unroll
-                    for (int q = 0; q < 3; ++q) acc = mfma32(Wr[p][q], bfrag[q], acc);
+                for (int v = 0; v < 16; ++v) acc[v] = sum[v] + bias16[v];
                 if (x < g.w)
                     store_tile_bf16(out + (((int64_t)n * g.h + y) * g.w + x) * C + cb * 32 + half * 16, acc, true);
                 if (sample) {

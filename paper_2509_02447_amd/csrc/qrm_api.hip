@@ -318,7 +318,8 @@ qrm_status get_slot(qrm_ctx *c, hipStream_t s, size_t bytes, QrmSlot **out)
         // Diagnostic (qrm_diag_set_flags): a new workspace filled with 0xFF bytes (NaN as bf16 / fp32), so that
         // a kernel reading something no kernel wrote shows up in the results.
         if (c->diag_flags & QRM_DIAG_POISON_WORKSPACE) {
-            e = hipMemsetAsync(slot->ws, 0xFF, bytes, s);
+            const int fill = (c->diag_flags >> 8) & 0xFF; // another fill byte may ride in bits 8..15
+            e = hipMemsetAsync(slot->ws, fill ? fill : 0xFF, bytes, s);
             if (e != hipSuccess) return hip_fail(c, e, "hipMemsetAsync(workspace poison)");
         }
         // The block of zeros the convolutions read their padding from; written once per allocation, on

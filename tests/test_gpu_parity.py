@@ -493,12 +493,14 @@ def test_results_are_reproducible_bit_for_bit(qrm):
     """Two calls give the same bytes: every sum inside the kernels is formed in a fixed order.  On the fused path
     (64 channels) that order depends on the image alone, so other splits of the batch into micro-batches give the
     same bytes too; on the single-block path (32 channels) a split deals an image's strips to other workgroups, and
-    the last fp32 bits of the channel sums may then differ."""
-    for name, N, mbs in (("C2", 1300, (0, 300, 1024)), ("C1", 300, (0, 7))):
+    the last fp32 bits of the channel sums may then differ.  (The wide-tile cases launch many co-resident workgroups
+    of the first-layer kernel per compute unit: matrix results read too early once showed there as run-to-run
+    differences of one bf16 step.)"""
+    for name, N, mbs in (("C2", 1300, (0, 300, 1024)), ("C1", 300, (0, 7)), ("C3", 3, (0,)), ("C4", 40, (0,))):
         cfg = synth.CONFIGS[name]
         imgs = synth.images(cfg, 0, N, threads=HOST_THREADS)
-        fld = synth.field_images(cfg, 100, 40)
-        imgs[::N // 40][:40] = fld
+        if N >= 40:
+            imgs[::N // 40][:40] = synth.field_images(cfg, 100, 40)
         off = synth.offsets(cfg, 0, N)
         ctx = qrm.Context(weights=synth.config_weights(cfg), rs=rs_dict(cfg))
         runs = []
