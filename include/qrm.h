@@ -227,6 +227,27 @@ QRM_API qrm_status qrm_detect(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, 
                       uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
 
 /*
+ * qrm_detect for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same results as qrm_detect, but the workspace
+ * (activation buffers of a micro-batch, channel statistics, packed symbols) is a fixed array of
+ * QRM_STATIC_SCRATCH_BYTES inside the library's device image instead of memory taken from the context, and
+ * the call neither allocates nor frees anything, creates no event or stream, and records no memset (the
+ * array's block of zeros is cleared by a kernel).  The micro-batch is the largest one that fits the array
+ * (e.g. 56 images of 64 x 64 tiles at 64 channels); qrm_set_micro_batch and the profiling switch do not apply.
+ * Every call on a device shares that device's one array (each device holds its own copy until the process
+ * ends): calls that overlap in time on one device, on whatever streams or contexts, race.  Calls on one
+ * stream, one after the other, are safe.
+ * Errors: as qrm_detect, plus QRM_E_UNSUPPORTED when the sizes do not fit the array (a single tile's
+ * activations, tile*tile*channels*2 bytes, must fit twice beside N*n symbol bytes: tiles up to about
+ * 500 x 500 at 64 channels), QRM_E_DEVICE when the array's address could not be looked up at qrm_create.
+ */
+#define QRM_STATIC_SCRATCH_BYTES (64u << 20)
+QRM_API qrm_status qrm_detect_static(qrm_ctx *ctx, const uint8_t *d_images, int64_t N, int32_t H, int32_t W,
+                                     const int32_t *d_off_yx, int32_t tile,
+                                     float *d_logits, uint8_t *d_bits,
+                                     uint8_t *d_msg, uint8_t *d_codeword, int8_t *d_nerr, void *stream);
+
+/*
  * Key verification (Section 4.3: the RS-corrected message is compared with the predetermined key;
  * Listing 1, `verify(recovered_key, secret_key)`; Table 2: the false-positive rate is held at 1e-6).
  * An image that carries no watermark yields message bits that agree with the key like fair coin

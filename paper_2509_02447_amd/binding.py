@@ -40,7 +40,7 @@ class _RsDesc(C.Structure):
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
            "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
-           "qrm_profile_enable", "qrm_profile_read", "qrm_release_stream", "qrm_version"]
+           "qrm_profile_enable", "qrm_profile_read", "qrm_release_stream", "qrm_detect_static", "qrm_version"]
 DIAG_EXPORTS = ["qrm_diag_set_flags", "qrm_diag_matrix_rate"]      # include/qrm_diag.h: bench and test tooling
 
 QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE = 1, 2
@@ -87,6 +87,8 @@ def load_library():
     lib.qrm_rs_decode.restype = C.c_int
     lib.qrm_detect.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.qrm_detect.restype = C.c_int
+    lib.qrm_detect_static.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.qrm_detect_static.restype = C.c_int
     lib.qrm_detect_host.argtypes = [vp, C.POINTER(vp), i32, i32, i32, i32, C.POINTER(vp), i32, i32, vp, vp, vp]
     lib.qrm_detect_host.restype = C.c_int
     lib.qrm_key_threshold.argtypes = [i32, C.c_double]
@@ -272,6 +274,12 @@ class Context:
         self._check(self._lib.qrm_detect(self._h, _dptr(d_images), int(N), int(H), int(W), _dptr(d_off_yx),
                                          int(tile), _dptr(d_logits), _dptr(d_bits), _dptr(d_msg), _dptr(d_codeword),
                                          _dptr(d_nerr), _stream_handle(stream)))
+
+    def qrm_detect_static(self, d_images, N, H, W, d_off_yx, tile, d_logits, d_bits, d_msg, d_codeword, d_nerr,
+                          stream=None):
+        self._check(self._lib.qrm_detect_static(self._h, _dptr(d_images), int(N), int(H), int(W), _dptr(d_off_yx),
+                                                int(tile), _dptr(d_logits), _dptr(d_bits), _dptr(d_msg),
+                                                _dptr(d_codeword), _dptr(d_nerr), _stream_handle(stream)))
 
     def qrm_detect_host(self, h_chunks, chunk_images, H, W, h_off_chunks, tile, depth, h_msg, h_codeword, h_nerr):
         """h_chunks / h_off_chunks: sequences of host buffers (pinned CPU tensors or numpy arrays), one per chunk."""

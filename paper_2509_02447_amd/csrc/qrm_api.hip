@@ -522,6 +522,10 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
     }
     hipError_t e = hipSetDevice(device);
     if (e != hipSuccess) return hip_fail(nullptr, e, "hipSetDevice");
+    // once per device, with that device current: the address of the static workspace of qrm_detect_static
+    // (a failure is reported by that entry point, not here)
+    (void)static_scratch_init(device);
+    (void)hipGetLastError();
 
     qrm_ctx *c = new qrm_ctx();
     c->device = device;

@@ -94,6 +94,9 @@ qrm_status run_extractor(qrm_ctx *c, uint8_t *base, const WsLayout &L, TileSrc s
 qrm_status check_detect_args(qrm_ctx *c, const uint8_t *d_images, int64_t N, int32_t H, int32_t W, int32_t tile,
                              uint8_t *d_msg, int8_t *d_nerr, bool verify, int32_t *d_matches);
 
+// qrm_noalloc.hip: looks up the device address of the static workspace on `device` (which must be current)
+hipError_t static_scratch_init(int device);
+
 inline size_t symbols_offset(const WsLayout &L) { return kZeroBytes + 2 * L.act + L.partial + 2 * L.stats + L.seam; }
 
 } // namespace qrm
