@@ -21,6 +21,10 @@ extern "C" {
                                        fp32): a kernel that reads workspace bytes no kernel wrote shows in the
                                        results; bits 8..15 of the flags, when not zero, give another fill byte */
 
+#define QRM_DIAG_FUSE_ALWAYS 4      /* run the fused schedule on wide tiles (more than 64 columns) also when a launch
+                                       has too few images to fill the compute units that way (tests of that path on
+                                       small batches) */
+
 /* Sets the context's diagnostic flags (0 = production behaviour).  Affects calls made afterwards. */
 QRM_API qrm_status qrm_diag_set_flags(qrm_ctx *ctx, int32_t flags);
 

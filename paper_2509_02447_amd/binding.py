@@ -43,7 +43,7 @@ EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch",
            "qrm_profile_enable", "qrm_profile_read", "qrm_release_stream", "qrm_detect_static", "qrm_version"]
 DIAG_EXPORTS = ["qrm_diag_set_flags", "qrm_diag_matrix_rate"]      # include/qrm_diag.h: bench and test tooling
 
-QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE = 1, 2
+QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE, QRM_DIAG_FUSE_ALWAYS = 1, 2, 4
 (QRM_PROFILE_PAIR_FIRST, QRM_PROFILE_PAIR_MID, QRM_PROFILE_PAIR_LAST, QRM_PROFILE_BLOCK_FIRST, QRM_PROFILE_BLOCK_MID,
  QRM_PROFILE_BLOCK_LAST, QRM_PROFILE_HEAD, QRM_PROFILE_RS_DECODE, QRM_PROFILE_KINDS) = range(9)
 PROFILE_KIND_NAMES = ["pair_first", "pair_mid", "pair_last", "block_first", "block_mid", "block_last", "head", "rs_decode"]

@@ -136,13 +136,13 @@ __device__ __forceinline__ lrow_t lds_address(const void *p)
 // pieces w, w+4, ..., so the per-lane column decoding is done once per strip, not once per load.
 // Pixels outside the tile must read as zero (zero padding of the convolution): rows above / below the
 // tile, halo columns outside it, and the padding slots of a pixel all load from the block of zeros that
-// opens the workspace (offset 0 from `ws`).  All sources are addressed as ws + 32-bit byte offset.
+// opens the workspace (`ws`).  A pixel is addressed as the image's base `img` + a 32-bit byte offset.
 // Window rows first_row..kRows+1 are loaded; window row r goes to row slot (ring_pos + r) mod nslot.
 // The caller waits (s_waitcnt vmcnt) and passes a barrier before anyone reads the rows.
 constexpr uint32_t kSlotZero = 0xffffffffu; // lane loads zeros
 
 template <int C>
-__device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *ws, uint32_t img_off, int h, int w,
+__device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *ws, const uint8_t *img, int h, int w,
                                                   int y0, int x0, int wave, int lane, int first_row = 0,
                                                   int ring_pos = 0, int nslot = kRows + 2)
 {
@@ -160,14 +160,14 @@ __device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *w
         if (r < 2 && r < first_row) continue;                       // already in LDS (or known to be zero there)
         const int gy = y0 - 1 + r;                                  // same for the whole workgroup
         const bool rowok = gy >= 0 && gy < h;
-        const uint32_t rowoff = img_off + (uint32_t)(gy * w * C * 2);
+        const uint32_t rowoff = (uint32_t)(gy * w * C * 2);
         const int rslot = (ring_pos + r) % nslot;
 #pragma unroll
         for (int qi = 0; qi < K::QPW; ++qi) {
             const int q = wave + 4 * qi;                            // same for the whole wavefront
             if (4 * qi + 3 < K::PIECES || q < K::PIECES) {
-                const uint32_t off = (rowok && coff[qi] != kSlotZero) ? rowoff + coff[qi] : 0u;
-                __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(lds + rslot * K::ROWB + q * 1024), 16, 0, 0);
+                const uint8_t *p = (rowok && coff[qi] != kSlotZero) ? img + (rowoff + coff[qi]) : ws;
+                __builtin_amdgcn_global_load_lds((gptr_t)p, (lptr_t)(lds + rslot * K::ROWB + q * 1024), 16, 0, 0);
             }
         }
         __builtin_amdgcn_sched_barrier(0); // one row's addresses at a time
@@ -326,7 +326,7 @@ template <int RW, bool LAST>
 __device__ __forceinline__ void strip_statistics(const f32x16 (&acc)[RW], const float *si, float *my_stat, int x, int yw,
                                                  int h, int w, int px)
 {
-    const bool colok = x < w;
+    const bool colok = (uint32_t)x < (uint32_t)w; // (x = -1: the column left of a wide tile's first block)
     const int rl = h - 1 - yw; // image row h-1 relative to this wavefront's rows
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -416,7 +416,7 @@ struct MidRing {
 //   first strip of a new image : 5 rows (the row above the tile is zero - and so is the last row the
 //                                previous strip loaded, which lay below its tile), wstart = base - 1
 template <int C, int MODE>
-__global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
+__global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8_t *__restrict__ ws, size_t in_off,
                                                                      ConvGeom g, const bf16_t *__restrict__ wfrag,
                                                                      const float *__restrict__ bias, StatArgs st,
                                                                      bf16_t *__restrict__ out)
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
     if (ns <= 0) return;
     const int out_slot = st.per >= tpi ? 0 : (t_begin % tpi) / st.per;
     const lrow_t lbase = lds_address(lds) + (xb * 32 + px) * K::PS + half * 16;
-    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
+    const size_t img_bytes = (size_t)g.h * g.w * C * 2;
 
     // ---- geometry of the strips of the run (tile order: image, column block, strip), kept as counters
     // that are advanced once per phase; all wave-uniform
@@ -488,7 +488,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
     Geo gp = gc;                                                                          // strip p - 1 (from phase 1 on)
 
     auto issue = [&](const Geo &q) {
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)q.n * img_bytes, g.h, g.w, q.strip * kRows, q.colblk * kTileW, w4,
+        issue_strip_loads<C>(lds, ws, ws + in_off + (size_t)q.n * img_bytes, g.h, g.w, q.strip * kRows, q.colblk * kTileW, w4,
                              pin_in_loop(lane), first_row(q), wstart(q), NSLOT);
     };
     // s_init[n & 3][o] = bias[o] + sum_c rsum[c][o] * mean_n[c], by the four wavefronts of one group:
@@ -553,8 +553,9 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
         // is ever alive next to the weights.
         const float *si = &s_init[n & 3][cb * 32 + half * 16];
         if (MODE == MODE_MID) {
-            // element offset of this lane's first row; the activation buffer is below 2^31 elements
-            const uint32_t e0 = (uint32_t)(((n * g.h + yw) * g.w + x) * C + cb * 32 + half * 16);
+            // the image's activations (same for the whole workgroup) + element offset of this lane's first row
+            bf16_t *out_img = out + (size_t)n * g.h * g.w * C;
+            const uint32_t e0 = (uint32_t)((yw * g.w + x) * C + cb * 32 + half * 16);
             const bool full = y0 + kRows <= g.h && x0 + kTileW <= g.w; // same for the whole workgroup
 #pragma unroll
             for (int hq = 0; hq < 2; ++hq) { // 8 channels = one 16-byte store per row
@@ -566,7 +567,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
                     pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
                     pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
                     pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
-                    bf16_t *dst = out + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
+                    bf16_t *dst = out_img + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
                     if (full) *(u32x4 *)dst = pk;
                     else if (yw + r < g.h && x < g.w) *(u32x4 *)dst = pk;
                     __builtin_amdgcn_sched_barrier(0); // one store at a time keeps the temporaries few
@@ -641,7 +642,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 }
 
 // ------------------------------------------------------------------------------------------------
-// Two consecutive C -> C blocks in one kernel (tiles of at most one column block, C = 64).
+// Two consecutive C -> C blocks in one kernel (C = 64).
 //
 // conv_mid is bound by activation traffic as much as by the matrix cores (288 FLOP per byte against a
 // machine balance of ~310).  Here the activations between the two blocks never leave the CU: a
@@ -663,15 +664,32 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
 // (output, input) channel pair cancel (error feedback over the taps): its input never exists as a whole
 // image, so there are no channel means to correct its bias with.
+//
+// WIDE (tiles wider than 64 columns): the rings stay 66 pixels wide and a workgroup walks through its image
+// one column block of 64 after the other, left to right, each block top to bottom ("unit" = (image, column
+// block); the units of a workgroup form one stream of row pairs as the images do above).  In block b group A
+// computes intermediate columns [64 b, 64 b + 64) from input columns [64 b - 1, 64 b + 65), and group B computes
+// output columns [64 b - 1, 64 b + 63): one column to the left, so that everything B needs lies at or left of
+// A's newest column.  The two intermediate columns left of A's (64 b - 2, 64 b - 1) were computed in block
+// b - 1: A writes its last two columns of every row to a small buffer in global memory (the "seam", 256 bytes a
+// row, per workgroup, two of them used alternately), from which they come back into ring pixels 0 and 1 a whole
+// column block later (for b = 0 those pixels are zero: the padding).  Nothing is computed twice and no
+// matrix tile is partly empty.  What is left over is the tile's last column when the width is a multiple of 64:
+// the intermediate columns w-2, w-1 of every row go to a per-image seam buffer and conv_seam_kernel, a small
+// launch behind this one, computes output column w-1 from them.
 // ------------------------------------------------------------------------------------------------
 constexpr int kPairRing = 8;
+constexpr int kSeamRowBytes = 2 * 64 * 2; // two pixels of 64 bf16 channels: what one row hands over
 
 struct PairArgs {
     const float *tin;   // records of the input's channel sums [n_img][in_slots][stat_rec(C,1)], or nullptr
     int in_slots;
     const float *rsum;  // [c_in][c_out] residual-weight sums of the first block (fp32), or nullptr
-    float *tout;        // records of the output's channel sums [n_img][kPairSub][stat_rec(C, 1 or 9)], or nullptr
+    float *tout;        // records of the output's channel sums [n_img][out_slots][stat_rec(C, 1 or 9)], or nullptr
+    int out_slots;      // records per image (the first kPairSub of them are written here)
     int ipw;            // images per workgroup
+    uint8_t *seam;      // WIDE: [workgroup][2][2 S rows][2 pixels][C] bf16, columns handed to the next column block
+    uint8_t *seam_last; // WIDE, width a multiple of 64: [image][2 S rows][2 pixels][C], intermediate columns w-2, w-1
 };
 constexpr int kPairSub = 2; // statistics records per image: one per pixel-block pair of wavefronts of group B
 
@@ -680,8 +698,11 @@ constexpr int kPairSub = 2; // statistics records per image: one per pixel-block
 //        C -> C block; `src` replaces ws / in_off, wfragA holds that block's fragments.
 // LASTB: the second block is the network's last block: no activations are written, its records carry the
 //        nine border-aware channel sums (see strip_statistics).
-template <int C, bool FIRST, bool LASTB>
-__global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__restrict__ ws, uint32_t in_off, TileSrc src,
+// WIDE : tiles of more than one column block (see above); the other instantiations keep the straight-line code
+//        of the one-block case.
+// zeros: kZeroBytes of zeros (the source of the padding); in: the input activations of the launch.
+template <int C, bool FIRST, bool LASTB, bool WIDE>
+__global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__restrict__ zeros, const uint8_t *__restrict__ in, TileSrc src,
                                                            ConvGeom g, const bf16_t *__restrict__ wfragA,
                                                            const bf16_t *__restrict__ wfragB,
                                                            const float *__restrict__ biasA,
@@ -707,6 +728,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     // [buffer = row pair parity][wavefront][row * 4 + channel quad][lane] x 4 floats
     __shared__ __attribute__((aligned(16))) float s_accx[FIRST ? 2 * 4 * 8 * 256 : 4];
     constexpr int kFinishGroup = FIRST ? 0 : 1; // the group that finishes output rows (stores, statistics)
+    constexpr int kSkew = WIDE ? 1 : 0;         // group B's columns lie this far left of group A's
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -730,7 +752,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     const int n_begin = vb * st.ipw, n_end = min(g.n_img, n_begin + st.ipw);
     if (n_begin >= n_end) return;
     const int S = (g.h + 1) / 2;
-    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
+    const int J = WIDE ? g.colblks : 1;           // column blocks of a tile
+    const size_t img_bytes = (size_t)g.h * g.w * C * 2;
+    const uint32_t row_bytes = (uint32_t)(g.w * C * 2);
     const lrow_t in_base = lds_address(ring_in) + (xb * 32 + px) * K::PS + half * 16;
     const lrow_t mid_base = lds_address(ring_mid) + (xb * 32 + px) * K::PS + half * 16;
     const int sample_phase = min(3, g.strips - 1);
@@ -741,26 +765,30 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     // slot in an image row (kSlotZero: zeros; kSlotNone: no slot - the last piece of a row is partial, the
     // next row starts right behind it).
     constexpr int QPW = (PIECES + 3) / 4;
-    constexpr uint32_t kSlotNone = 0xfffffffeu;
-    uint32_t lane_off[QPW];
+    // per lane and piece: byte offset of the lane's slot in an image row for column block 0 (negative for the
+    // halo column left of the tile), or a mark far below zero: no slot (the last piece of a row is partial, the
+    // next row starts right behind it), or one of a pixel's padding slots (always zero)
+    constexpr int32_t kSlotNone = INT32_MIN, kSlotPad = INT32_MIN / 2;
+    int32_t lane_off[QPW];
 #pragma unroll
     for (int k = 0; k < QPW; ++k) {
         const int sl = (w4 + 4 * k) * 64 + lane;
         const int col = sl / K::SPP, cpos = sl - col * K::SPP;
-        const int gx = col - 1;
-        lane_off[k] = sl >= SLOTS ? kSlotNone : (cpos < C / 8 && gx >= 0 && gx < g.w) ? (uint32_t)((gx * C + cpos * 8) * 2) : kSlotZero;
+        lane_off[k] = sl >= SLOTS ? kSlotNone : (cpos < C / 8 ? ((col - 1) * C + cpos * 8) * 2 : kSlotPad);
     }
-    auto issue_row = [&](int n, int y, int vrow) { // vrow: the row's place in the stream of images (see the main loop)
+    auto issue_row = [&](int n, int blk, int y, int vrow) { // vrow: the row's place in the stream of units (see the main loop)
         const bool rowok = y >= 0 && y < g.h;
-        const uint32_t rowoff = in_off + (uint32_t)n * img_bytes + (uint32_t)(y * g.w * C * 2);
+        const uint8_t *rowp = in + (size_t)n * img_bytes + (size_t)(rowok ? y : 0) * row_bytes; // same for the whole workgroup
+        const int32_t xoff = blk * (kTileW * C * 2);
         uint8_t *dst = ring_in + slot_of(vrow) * ROWB;
 #pragma unroll
         for (int k = 0; k < QPW; ++k) {
             const int q = w4 + 4 * k;
             if (q < PIECES) {
-                const uint32_t off = (rowok && lane_off[k] < kSlotNone) ? rowoff + lane_off[k] : 0u;
+                const int32_t o = lane_off[k] + xoff; // the marks stay far below zero
+                const uint8_t *p = (rowok && (uint32_t)o < row_bytes) ? rowp + o : zeros;
                 if (lane_off[k] != kSlotNone)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(ws + off), (lptr_t)(dst + q * 1024), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr_t)p, (lptr_t)(dst + q * 1024), 16, 0, 0);
             }
         }
     };
@@ -800,11 +828,11 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     // outside) and fetches the aligned dword that holds the byte (it never leaves the byte's page): a load under
     // a lane mask, or a byte load with its widening, would be waited for on the spot, and a step would then
     // contain two round trips to memory instead of hiding them behind its matrix work.
-    auto pixel_fetch = [&](const uint8_t *tile0, int y0, int e, bool &inside, uint32_t &shift) -> uint32_t {
+    auto pixel_fetch = [&](const uint8_t *tile0, int x0, int y0, int e, bool &inside, uint32_t &shift) -> uint32_t {
         const int ec = min(e, 2 * kRowElems - 1);
         const int row = ec / kRowElems, rem = ec - row * kRowElems;
         const int c = rem / kHaloW, col = rem - c * kHaloW;
-        const int ty = y0 + row, tx = col - 1;
+        const int ty = y0 + row, tx = x0 + col - 1;
         inside = e < 2 * kRowElems && ty >= 0 && ty < g.h && tx >= 0 && tx < g.w;
         const int tyc = clampi(ty, 0, g.h - 1), txc = clampi(tx, 0, g.w - 1);
         const uintptr_t p = (uintptr_t)(tile0 + ((int64_t)c * plane + (int64_t)tyc * src.W + txc));
@@ -838,32 +866,38 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         if (tid < C) s_initA[tid] = biasA[tid];
         for (int i = tid; i < kPairRing * kHaloW; i += 256) s_pix[i / kHaloW][i % kHaloW][3] = 0; // the padding channel
     }
+    if (!WIDE) // (WIDE: pixels 0 and 1 are rewritten in every step, 2 .. 65 by group A)
     for (int i = tid; i < kPairRing * 2 * (K::PS / 16); i += 512) { // columns -1 and w.. stay zero for good
         const int row = i / (2 * (K::PS / 16)), rem = i - row * 2 * (K::PS / 16);
         const int side = rem / (K::PS / 16), sl = rem - side * (K::PS / 16);
         *(u32x4 *)(ring_mid + row * ROWB + (side ? (kHaloW - 1) : 0) * K::PS + sl * 16) = (u32x4){0u, 0u, 0u, 0u};
     }
 
-    // The images of a workgroup form one stream of row pairs: image i takes P = S + 1 steps (S row pairs and
-    // the pair of padding rows below the tile, which is also the padding row above the next image), and
-    // virtual row 2 P i + y stands for row y of image i in both rings.  In step sigma group A is at position
-    // sigma of the stream, group B at sigma - 2, the epilogue of B's rows at sigma - 3, the loads at
-    // sigma + 2: nothing drains between images.
+    // The units (image, column block) of a workgroup form one stream of row pairs: unit u takes P = S + 1 steps
+    // (S row pairs and the pair of padding rows below the tile, which is also the padding row above the next
+    // unit), and virtual row 2 P u + y stands for row y of unit u in both rings.  In step sigma group A is at
+    // position sigma of the stream, group B at sigma - 2, the epilogue of B's rows at sigma - 3, the loads at
+    // sigma + 2: nothing drains between units.
     struct Pos {
-        int i, s; // image within the workgroup, step within the image
+        int i, b, s; // image within the workgroup, column block within the image, step within the unit
     };
     const int P = S + 1;
     const int n_cnt = n_end - n_begin;
-    auto pos_of = [P](int sigma) {
-        const int i = sigma >= 0 ? sigma / P : -((P - 1 - sigma) / P);
-        return Pos{i, sigma - i * P};
+    auto pos_of = [P, J](int sigma) {
+        const int u = sigma >= 0 ? sigma / P : -((P - 1 - sigma) / P);
+        const int i = u >= 0 ? u / J : -((J - 1 - u) / J);
+        return Pos{i, u - i * J, sigma - u * P};
     };
-    auto advance = [P](Pos &p) {
+    auto advance = [P, J](Pos &p) {
         if (++p.s == P) {
             p.s = 0;
-            ++p.i;
+            if (++p.b == J) {
+                p.b = 0;
+                ++p.i;
+            }
         }
     };
+    auto next_unit = [J](const Pos &p) { return p.b + 1 == J ? Pos{p.i + 1, 0, 0} : Pos{p.i, p.b + 1, 0}; };
     Pos pa = pos_of(0), pb = pos_of(-2), pf = pos_of(-3), pl = pos_of(2), p1 = pos_of(1);
     auto tile_origin = [&](int n) {
         int oy = 0, ox = 0;
@@ -886,15 +920,16 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 for (int k = 0; k < 2; ++k) {
                     bool inside;
                     uint32_t shift;
-                    const uint32_t v = pixel_fetch(tile0, y0, tid + 256 * k, inside, shift);
+                    const uint32_t v = pixel_fetch(tile0, 0, y0, tid + 256 * k, inside, shift);
                     pixel_store(y0, tid + 256 * k, v, shift, inside);
                 }
         }
     } else {
 #pragma unroll 1
         for (int v = -1 + grp; v <= 4; v += 2) { // first, so that they travel while the correction is computed
-            const int i = (v + 1) / (2 * P);     // a tile of one or two rows: rows 3, 4 of the stream are the next image's
-            if (i < n_cnt) issue_row(n_begin + i, v - 2 * P * i, v);
+            const int u = (v + 1) / (2 * P);     // a tile of one or two rows: rows 3, 4 of the stream are the next unit's
+            const int i = u / J;
+            if (i < n_cnt) issue_row(n_begin + i, u - i * J, v - 2 * P * u, v);
         }
         if (grp == 0) prepare_init(n_begin);
     }
@@ -903,18 +938,21 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();
 
-    // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 of image n held in `a`;
-    // after the last row pair of an image its channel sums go to its records and the accumulators are cleared
-    auto finish = [&](const f32x16 (&a)[RW], int n, int j) {
+    // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 of column block blk of
+    // image n held in `a`; after the last row pair of an image its channel sums go to its records and the
+    // accumulators are cleared
+    auto finish = [&](const f32x16 (&a)[RW], int n, int blk, int j) {
         const int ln = pin_in_loop(tid & 63);
         const int pxl = ln & 31, hf = ln >> 5;
-        const int x = xb * 32 + pxl;
+        const int x_lo = blk * kTileW - kSkew;     // first of the workgroup's 64 output columns (-1 in block 0 of a wide tile)
+        const int x = x_lo + xb * 32 + pxl;
         const float *si = &s_biasB[cb * 32 + hf * 16];
         if (!LASTB) {
-            // address = uniform start of the row pair + what the lane adds (the same in every step)
-            bf16_t *rows = out + (uint32_t)((n * g.h + 2 * j) * g.w * C);
-            const uint32_t le = (uint32_t)(x * C + cb * 32 + hf * 16);
-            const bool full = 2 * j + RW <= g.h && g.w == kTileW; // same for the whole workgroup
+            // address = uniform start of the row pair + what the lane adds
+            bf16_t *rows = out + ((size_t)n * g.h + 2 * j) * ((size_t)g.w * C);
+            const int le = x * C + cb * 32 + hf * 16;
+            const int rstride = g.w * C;
+            const bool full = 2 * j + RW <= g.h && x_lo >= 0 && x_lo + kTileW <= g.w; // same for the whole workgroup
             if (full) { // the common case: straight-line code, no predicates
 #pragma unroll
                 for (int hq = 0; hq < 2; ++hq) {
@@ -926,7 +964,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
                         pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
                         pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
-                        *(u32x4 *)(rows + (le + (uint32_t)(r * kTileW * C + 8 * hq))) = pk;
+                        *(u32x4 *)(rows + (le + r * rstride + 8 * hq)) = pk;
                     }
                 }
             } else {
@@ -940,7 +978,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
                         pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
                         pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
-                        if (2 * j + r < g.h && x < g.w) *(u32x4 *)(rows + (le + (uint32_t)(r * g.w * C + 8 * hq))) = pk;
+                        if (2 * j + r < g.h && (uint32_t)x < (uint32_t)g.w) *(u32x4 *)(rows + (le + r * rstride + 8 * hq)) = pk;
                     }
                 }
             }
@@ -948,12 +986,13 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
             strip_statistics<RW, LASTB>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
             if (cb == 0 && ln == 0) {
-                const int rows = max(0, min(RW, g.h - 2 * j)), cols = max(0, min(32, g.w - xb * 32));
+                const int rows = max(0, min(RW, g.h - 2 * j));
+                const int cols = max(0, min(x_lo + xb * 32 + 32, g.w) - max(x_lo + xb * 32, 0));
                 s_cnt[w4] += (float)(rows * cols);
             }
         }
-        if (st.tout && j == S - 1) { // what this wavefront gathered for the image (its own part of s_stat)
-            float *rec = st.tout + ((int64_t)n * kPairSub + xb) * stat_rec(C, NQ);
+        if (st.tout && j == S - 1 && blk == J - 1) { // what this wavefront gathered for the image (its own part of s_stat)
+            float *rec = st.tout + ((int64_t)n * st.out_slots + xb) * stat_rec(C, NQ);
             if (ln < 32) {
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
@@ -969,29 +1008,33 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     };
 
     f32x16 acc[RW];
-    const int n_steps = n_cnt * P + 2;
+    const int n_steps = n_cnt * J * P + 2;
+    const size_t seam_half = (size_t)(2 * S) * kSeamRowBytes; // one of a workgroup's two seam buffers
 #pragma unroll 1
     for (int sg = 0; sg < n_steps; ++sg) {
         const bool fin = pf.i >= 0 && pf.i < n_cnt && pf.s < S; // rows accumulated in the previous step wait for their epilogue
         if (grp == 0) {
             const int ln = pin_in_loop(tid & 63);
             const int pxl = ln & 31, hf = ln >> 5;
-            const int x = xb * 32 + pxl;
+            const int xl = xb * 32 + pxl;          // this lane's column within the block
+            const int x = pa.b * kTileW + xl;      // and within the tile
             // FIRST: the raw pixels of virtual rows 2sg+3, 2sg+4 (window of step sg+1) start their way into registers
             uint32_t pv[2] = {0, 0}, psh[2] = {0, 0};
             bool pin[2] = {false, false};
             bool fetch = false;
             if (FIRST && p1.i < n_cnt) {
-                int y0 = 2 * p1.s + 1;
+                int y0 = 2 * p1.s + 1, fb = p1.b;
                 fetch = true;
-                if (p1.s == S) { // rows -1, 0 of the next image
-                    fetch = p1.i + 1 < n_cnt;
+                if (p1.s == S) { // rows -1, 0 of the next unit
+                    const Pos nu = next_unit(p1);
+                    fetch = nu.i < n_cnt;
                     y0 = -1;
-                    if (fetch) tile0 = tile_origin(n_begin + p1.i + 1);
+                    fb = nu.b;
+                    if (fetch && nu.b == 0) tile0 = tile_origin(n_begin + nu.i);
                 }
                 if (fetch) {
 #pragma unroll
-                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, y0, tid + 256 * k, pin[k], psh[k]);
+                    for (int k = 0; k < 2; ++k) pv[k] = pixel_fetch(tile0, fb * kTileW, y0, tid + 256 * k, pin[k], psh[k]);
                 }
             }
             if (pa.i < n_cnt && pa.s < S) {
@@ -1033,6 +1076,17 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
                 // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
                 const float *si = &s_initA[cb * 32 + hf * 16];
+                // WIDE: the last two columns of the block also go to the seam: the workgroup's own (for its next
+                // column block) or the image's (the tile's last two columns, for conv_seam_kernel)
+                uint8_t *seam_rows = nullptr;
+                if (WIDE) {
+                    // (FIRST: the stores of the previous step - this group's only ones - are done before this
+                    // step's follow; a seam row is read a whole unit, at least two steps, after it was written)
+                    if (FIRST) __builtin_amdgcn_s_waitcnt(kWaitVm0);
+                    if (pa.b + 1 < J) seam_rows = st.seam + ((size_t)blockIdx.x * 2 + (pa.b & 1)) * seam_half;
+                    else if (st.seam_last) seam_rows = st.seam_last + (size_t)(n_begin + pa.i) * seam_half;
+                    if (seam_rows) seam_rows += (size_t)(2 * pa.s) * kSeamRowBytes + (cb * 32 + hf * 16) * 2;
+                }
 #pragma unroll
                 for (int hq = 0; hq < 2; ++hq) {
                     const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
@@ -1045,7 +1099,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
                         pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
                         if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
-                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
+                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + kSkew + xl) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
+                        if (WIDE && seam_rows && xl >= kTileW - 2)
+                            *(u32x4 *)(seam_rows + r * kSeamRowBytes + (xl - (kTileW - 2)) * (C * 2) + 8 * hq * 2) = pk;
                     }
                 }
             } else if (pa.i < n_cnt) { // the rows below the tile: zero padding of the second block (and above the next image)
@@ -1053,9 +1109,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 for (int r = 0; r < RW; ++r)
 #pragma unroll
                     for (int hq = 0; hq < 2; ++hq)
-                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + x) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
+                        *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + kSkew + xl) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) =
                             (u32x4){0u, 0u, 0u, 0u};
-                if (!FIRST && pa.i + 1 < n_cnt) prepare_init(n_begin + pa.i + 1); // nobody reads s_initA in this step
+                if (!FIRST && pa.b == J - 1 && pa.i + 1 < n_cnt) prepare_init(n_begin + pa.i + 1); // nobody reads s_initA in this step
             }
             if (FIRST && fetch) { // their slots were last read two steps ago; before the stores below, which need not be waited for
 #pragma unroll
@@ -1071,11 +1127,25 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         const f32x4 v = *(const f32x4 *)(srcx + (r * 4 + q) * 256);
                         a[r][4 * q] = v[0]; a[r][4 * q + 1] = v[1]; a[r][4 * q + 2] = v[2]; a[r][4 * q + 3] = v[3];
                     }
-                finish(a, n_begin + pf.i, pf.s);
+                finish(a, n_begin + pf.i, pf.b, pf.s);
             }
         } else {
             const int ln = pin_in_loop(tid & 63);
-            if (!FIRST && fin) finish(acc, n_begin + pf.i, pf.s); // the rows accumulated in the previous step
+            if (WIDE && w4 == 0 && pa.i < n_cnt) {
+                // ring pixels 0 and 1 of the intermediate rows group A writes in this step: the two columns left
+                // of its block, from the seam of the block before (zeros in block 0 and in the padding rows);
+                // 2 x 9 slots per row, straight into LDS
+                const bool have = pa.b > 0 && pa.s < S;
+                const uint8_t *sp = st.seam + ((size_t)blockIdx.x * 2 + ((pa.b & 1) ^ 1)) * seam_half + (size_t)(2 * pa.s) * kSeamRowBytes;
+                const int spx = ln / K::SPP, sslot = ln - spx * K::SPP;
+#pragma unroll
+                for (int r = 0; r < RW; ++r) {
+                    const uint8_t *p = (have && sslot < C / 8) ? sp + r * kSeamRowBytes + spx * (C * 2) + sslot * 16 : zeros;
+                    if (ln < 2 * K::SPP)
+                        __builtin_amdgcn_global_load_lds((gptr_t)p, (lptr_t)(ring_mid + slot_of(2 * sg + r) * ROWB), 16, 0, 0);
+                }
+            }
+            if (!FIRST && fin) finish(acc, n_begin + pf.i, pf.b, pf.s); // the rows accumulated in the previous step
             if (pb.i >= 0 && pb.i < n_cnt && pb.s < S) {
                 lrow_t rowp[RW + 2];
 #pragma unroll
@@ -1099,13 +1169,14 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             __builtin_amdgcn_s_waitcnt(kWaitVm0);
             if (pl.i < n_cnt) {
                 const bool nxt = pl.s == S;
-                const int li = pl.i + (nxt ? 1 : 0);
-                if (li < n_cnt) {
-                    issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1), 2 * sg + 5);
-                    issue_row(n_begin + li, (nxt ? -1 : 2 * pl.s + 1) + 1, 2 * sg + 6);
+                const Pos lu = nxt ? next_unit(pl) : pl;
+                if (lu.i < n_cnt) {
+                    issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1), 2 * sg + 5);
+                    issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1) + 1, 2 * sg + 6);
                 }
             }
         }
+        if (WIDE && grp == 1 && w4 == 0) __builtin_amdgcn_s_waitcnt(kWaitVm0); // the seam columns have landed
         lds_barrier();
         advance(pa);
         advance(pb);
@@ -1115,10 +1186,95 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     }
 }
 
+// The last output column of a fused launch on a tile whose width is a multiple of 64 (see conv_pair_kernel,
+// WIDE): out[r][w-1] from the intermediate columns w-2, w-1 that group A left in the per-image seam buffer; the
+// column right of them is the zero padding, so only the taps dx = 0, 1 count.  One workgroup of two wavefronts
+// (one per 32 output channels) per 32 rows of an image; a lane's pixel is a row.  Operands come straight from
+// global memory: the launch is a fraction of a percent of the fused one's work.
+// LASTB: instead of activations the column's share of the nine border-aware channel sums, one record per
+// workgroup (record rec_first + its index within the image).
+template <int C, bool LASTB>
+__global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restrict__ seam_last, ConvGeom g,
+                                                        const bf16_t *__restrict__ wfragB, const float *__restrict__ biasB,
+                                                        float *__restrict__ tout, int out_slots, int rec_first,
+                                                        bf16_t *__restrict__ out)
+{
+    typedef MidCfg<C> K;
+    __shared__ float s_rec[LASTB ? stat_rec(C, 9) : 1];
+    const int lane = threadIdx.x & 63;
+    const int cb = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int px = lane & 31, half = lane >> 5;
+    const int tiles = (g.h + 31) / 32;
+    const int n = blockIdx.x / tiles, t = blockIdx.x - n * tiles;
+    const int r = t * 32 + px; // this lane's output row
+    const uint8_t *sl = seam_last + (size_t)n * (2 * ((g.h + 1) / 2)) * kSeamRowBytes;
+    const bf16x8 *wp = (const bf16x8 *)wfragB + (size_t)cb * 9 * K::KC * 64 + lane;
+    if (LASTB) {
+        for (int i = threadIdx.x; i < stat_rec(C, 9); i += 128) s_rec[i] = 0.f;
+        __syncthreads();
+    }
+    f32x16 sum = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy) {
+        const int y = r + dy - 1;
+        const bool ok = y >= 0 && y < g.h;
+#pragma unroll
+        for (int dx = 0; dx < 2; ++dx)
+#pragma unroll
+            for (int kc = 0; kc < K::KC; ++kc) {
+                u32x4 b = {0u, 0u, 0u, 0u};
+                if (ok) b = *(const u32x4 *)(sl + (size_t)y * kSeamRowBytes + dx * (C * 2) + (kc * 16 + half * 8) * 2);
+                sum = mfma32(wp[((dy * 3 + dx) * K::KC + kc) * 64], __builtin_bit_cast(bf16x8, b), sum);
+            }
+    }
+    const float *bp = biasB + cb * 32 + half * 16;
+    float val[16]; // bias added by ordinary vector instructions (see pack_bf16_relu)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) val[v] = sum[v] + bp[v];
+    if (!LASTB) {
+        if (r < g.h) {
+            bf16_t *dst = out + (((size_t)n * g.h + r) * g.w + (g.w - 1)) * C + cb * 32 + half * 16;
+            u32x4 lo, hi;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                lo[v] = pack_bf16_relu(val[2 * v], val[2 * v + 1], true);
+                hi[v] = pack_bf16_relu(val[8 + 2 * v], val[8 + 2 * v + 1], true);
+            }
+            *(u32x4 *)dst = lo;
+            *(u32x4 *)(dst + 8) = hi;
+        }
+    } else if (tout) {
+        // sums 0 (everything) and 4 (last column): all rows; 1 and 6 (first row, its right corner): row 0;
+        // 2 and 8 (last row, its right corner): row h-1.  Every entry has one writer.
+        const int ch = cb * 32 + half * 16;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float a = r < g.h ? fmaxf(val[v], 0.f) : 0.f;
+            const float tot = half_sum(a);
+            if (px == kSumLane) {
+                s_rec[0 * C + ch + v] = tot;
+                s_rec[4 * C + ch + v] = tot;
+            }
+            if (r == 0) {
+                s_rec[1 * C + ch + v] = a;
+                s_rec[6 * C + ch + v] = a;
+            }
+            if (r == g.h - 1) {
+                s_rec[2 * C + ch + v] = a;
+                s_rec[8 * C + ch + v] = a;
+            }
+        }
+        if (threadIdx.x == 0) s_rec[9 * C] = (float)max(0, min(32, g.h - t * 32));
+        __syncthreads();
+        float *rec = tout + ((int64_t)n * out_slots + rec_first + t) * stat_rec(C, 9);
+        for (int i = threadIdx.x; i < stat_rec(C, 9); i += 128) rec[i] = s_rec[i];
+    }
+}
+
 // Final conv C -> 64 output channels per grid.y slice, summed over the pixels of one (image, column
 // block).  partial[n][colblk*2 + xb][slice*64 + cb*32 + half*16 + v]
 template <int C, bool RELU>
-__global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__restrict__ ws, uint32_t in_off,
+__global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__restrict__ ws, size_t in_off,
                                                             ConvGeom g, int nbp,
                                                             const bf16_t *__restrict__ wfrag,
                                                             const float *__restrict__ bias,
@@ -1150,7 +1306,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
     lrow_t rowp[RW + 2];
 #pragma unroll
     for (int r = 0; r < RW + 2; ++r) rowp[r] = lds_address(lds) + r * K::ROWB + (xb * 32 + px) * K::PS + half * 16;
-    const uint32_t img_bytes = (uint32_t)(g.h * g.w * C * 2);
+    const size_t img_bytes = (size_t)g.h * g.w * C * 2;
 
     for (int t = t_begin; t < t_end; ++t) {
         const int colblk = t % g.colblks;
@@ -1163,7 +1319,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
         for (int v = 0; v < 16; ++v) { sum[0][v] = 0.f; sum[1][v] = 0.f; }
 
         __syncthreads();
-        issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, 0, x0, wave, lane);
+        issue_strip_loads<C>(lds, ws, ws + in_off + (size_t)n * img_bytes, g.h, g.w, 0, x0, wave, lane);
         for (int strip = 0; strip < g.strips; ++strip) {
             const int y0 = strip * kRows;
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -1173,7 +1329,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
                 else strip_mma<C, RW, true, true>(rowp, Wr, sum, g.h - y0);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
+                    issue_strip_loads<C>(lds, ws, ws + in_off + (size_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
             } else {
                 f32x16 acc[RW];
 #pragma unroll
@@ -1183,7 +1339,7 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
                 strip_mma<C, RW, false>(rowp, Wr, acc, RW);
                 __syncthreads();
                 if (strip + 1 < g.strips)
-                    issue_strip_loads<C>(lds, ws, in_off + (uint32_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
+                    issue_strip_loads<C>(lds, ws, ws + in_off + (size_t)n * img_bytes, g.h, g.w, y0 + kRows, x0, wave, lane);
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
                     if (y0 + r < g.h)
@@ -1549,7 +1705,7 @@ hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const
     return hipGetLastError();
 }
 
-hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
+hipError_t launch_conv_mid(const uint8_t *ws, size_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
                            const float *bias, const float *tin, int in_slots, const float *rsum, float *tout,
                            const Partition &part, bool last, bf16_t *out, hipStream_t s)
 {
@@ -1565,27 +1721,59 @@ hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g
     return hipGetLastError();
 }
 
-bool conv_pair_supported(int C, const ConvGeom &g) { return C == 64 && g.colblks == 1; }
+bool conv_pair_supported(int C, const ConvGeom &g) { return C == 64 && g.colblks >= 1; }
 
-int conv_pair_records_per_image() { return kPairSub; }
+int conv_pair_records_per_image(const ConvGeom &g, bool last)
+{
+    const bool seam_column = g.colblks > 1 && g.w % kTileW == 0; // conv_seam_kernel adds records of its own
+    return kPairSub + ((last && seam_column) ? (g.h + 31) / 32 : 0);
+}
 
-hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const TileSrc *first, const ConvGeom &g, int C,
+size_t conv_pair_seam_bytes(const ConvGeom &g, int num_cu)
+{
+    if (g.colblks <= 1) return 0;
+    const size_t half = (size_t)(2 * ((g.h + 1) / 2)) * kSeamRowBytes;
+    return half * (2 * (size_t)num_cu + (g.w % kTileW == 0 ? (size_t)g.n_img : 0));
+}
+
+template <bool FIRST, bool LASTB>
+static void launch_pair_variant(bool wide, dim3 grid, hipStream_t s, const uint8_t *zeros, const uint8_t *in, const TileSrc &src,
+                                const ConvGeom &g, const bf16_t *wfrag_a, const bf16_t *wfrag_b, const float *bias_a,
+                                const float *bias_b, const PairArgs &st, bf16_t *out)
+{
+    if (wide) hipLaunchKernelGGL((conv_pair_kernel<64, FIRST, LASTB, true>), grid, dim3(512), 0, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+    else hipLaunchKernelGGL((conv_pair_kernel<64, FIRST, LASTB, false>), grid, dim3(512), 0, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+}
+
+hipError_t launch_conv_pair(const uint8_t *zeros, const uint8_t *in, const TileSrc *first, const ConvGeom &g, int C,
                             const bf16_t *wfrag_a, const bf16_t *wfrag_b, const float *bias_a, const float *bias_b,
                             const float *tin, int in_slots, const float *rsum_a, float *tout, bool last, int num_cu,
-                            bf16_t *out, hipStream_t s)
+                            uint8_t *seam, bf16_t *out, hipStream_t s)
 {
     if (!conv_pair_supported(C, g)) return hipErrorInvalidValue;
+    const bool wide = g.colblks > 1;
+    const bool seam_column = wide && g.w % kTileW == 0;
+    if (wide && !seam) return hipErrorInvalidValue;
     const int ipw = (g.n_img + num_cu - 1) / num_cu;
-    const dim3 grid((g.n_img + ipw - 1) / ipw), block(512);
-    PairArgs st{tin, in_slots, rsum_a, tout, ipw};
+    const dim3 grid((g.n_img + ipw - 1) / ipw);
+    if ((int)grid.x > num_cu) return hipErrorInvalidValue; // the seam buffer holds num_cu workgroups
+    const size_t half = (size_t)(2 * ((g.h + 1) / 2)) * kSeamRowBytes;
+    uint8_t *seam_last = seam_column ? seam + 2 * (size_t)num_cu * half : nullptr;
+    const int out_slots = conv_pair_records_per_image(g, last);
+    PairArgs st{tin, in_slots, rsum_a, tout, out_slots, ipw, seam, seam_last};
     const TileSrc src = first ? *first : TileSrc{};
     if (first) {
-        if (last) hipLaunchKernelGGL((conv_pair_kernel<64, true, true>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
-        else hipLaunchKernelGGL((conv_pair_kernel<64, true, false>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        if (last) launch_pair_variant<true, true>(wide, grid, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        else launch_pair_variant<true, false>(wide, grid, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
     } else {
-        if (last) hipLaunchKernelGGL((conv_pair_kernel<64, false, true>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
-        else hipLaunchKernelGGL((conv_pair_kernel<64, false, false>), grid, block, 0, s, ws, in_off, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        if (last) launch_pair_variant<false, true>(wide, grid, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
+        else launch_pair_variant<false, false>(wide, grid, s, zeros, in, src, g, wfrag_a, wfrag_b, bias_a, bias_b, st, out);
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !seam_column) return e;
+    const dim3 sgrid((unsigned)g.n_img * (unsigned)((g.h + 31) / 32));
+    if (last) hipLaunchKernelGGL((conv_seam_kernel<64, true>), sgrid, dim3(128), 0, s, seam_last, g, wfrag_b, bias_b, tout, out_slots, kPairSub, out);
+    else hipLaunchKernelGGL((conv_seam_kernel<64, false>), sgrid, dim3(128), 0, s, seam_last, g, wfrag_b, bias_b, tout, out_slots, kPairSub, out);
     return hipGetLastError();
 }
 
@@ -1627,7 +1815,7 @@ size_t stat_record_floats(int C, int nq) { return (size_t)stat_rec(C, nq); }
 
 int conv_mid_records_per_workgroup(int C) { return kMidWaves / (C / 32); }
 
-hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
+hipError_t launch_conv_final(const uint8_t *ws, size_t in_off, const ConvGeom &g, int C, int nbp,
                              const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,
                              hipStream_t s)
 {

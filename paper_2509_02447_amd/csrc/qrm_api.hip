@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -215,8 +216,21 @@ int default_micro_batch(const qrm_ctx *c, int h, int w)
     const size_t per_img = (size_t)h * w * c->C * 2;
     size_t mb = ((size_t)512 << 20) / (per_img ? per_img : 1);
     if (mb < 64) mb = 64;
+    // The fused kernels give every compute unit whole images: tiles wider than one column block (where an image
+    // is a long run of work) get at least one image per compute unit, as long as a buffer stays below 4 GiB.
+    if (c->pairable && w > kTileW && mb < (size_t)c->num_cu && (size_t)c->num_cu * per_img <= ((size_t)4 << 30)) mb = c->num_cu;
     if (mb > 8192) mb = 8192;
     return (int)mb;
+}
+
+// Whether a launch of cnt images of h x w runs the fused schedule (two blocks per launch).  Narrow tiles always
+// do; wide ones only when the launch has images for at least half of the compute units (a workgroup of the fused
+// kernel takes whole images; the single-block kernel deals strips).
+bool use_fused(const qrm_ctx *c, int cnt, int w, int blocks)
+{
+    if ((c->diag_flags & QRM_DIAG_NO_FUSED_PAIRS) || !c->pairable || blocks < 2) return false;
+    if (w <= kTileW || (c->diag_flags & QRM_DIAG_FUSE_ALWAYS)) return true;
+    return 2 * cnt >= c->num_cu;
 }
 
 int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w, size_t act_budget)
@@ -225,9 +239,7 @@ int effective_micro_batch(const qrm_ctx *c, int64_t N, int h, int w, size_t act_
     int mb = c->micro_batch > 0 ? c->micro_batch : default_micro_batch(c, h, w);
     if (act_budget) mb = (int)std::min<size_t>(act_budget / (per_img ? per_img : 1), 65536);
     if ((int64_t)mb > N) mb = (int)(N > 0 ? N : 1);
-    // the single-block kernels address both activation buffers with 32-bit byte offsets from the workspace base
-    const size_t cap = kMaxImageActBytes / (per_img ? per_img : 1);
-    if ((size_t)mb > cap) mb = (int)cap;
+    if (per_img > kMaxImageActBytes) mb = 0; // the kernels address a pixel inside an image with 32-bit offsets
     return mb; // 0: not even one image fits
 }
 
@@ -255,9 +267,12 @@ WsLayout ws_layout(const qrm_ctx *c, int64_t N, int h, int w, bool want_symbols,
             if (cnt <= 0) continue;
             const Partition pf = make_partition(cnt, tpi, first_blocks(c));
             const Partition pm = make_partition(cnt, tpi, mid_blocks(c), conv_mid_records_per_workgroup(c->C));
+            const ConvGeom g{(int)cnt, h, w, (h + kRows - 1) / kRows, (w + kTileW - 1) / kTileW};
+            const int rp = c->pairable ? conv_pair_records_per_image(g, true) : 0;
             const int rf = pf.slots * pf.sub, rm = pm.slots * pm.sub;
-            const size_t r = (size_t)cnt * (rf > rm ? rf : rm);
+            const size_t r = (size_t)cnt * std::max(rp, std::max(rf, rm));
             if (r > recs) recs = r;
+            if (c->pairable) L.seam = std::max(L.seam, align_up(conv_pair_seam_bytes(g, c->num_cu)));
         }
         L.stats = align_up(recs * stat_record_floats(c->C, 9) * 4);
     }
@@ -368,7 +383,8 @@ qrm_status run_extractor(qrm_ctx *c, uint8_t *base, const WsLayout &L, TileSrc s
                          float *d_logits, uint8_t *d_bits, uint8_t *d_symbols, int m_sym, float *d_act, bool may_time,
                          hipStream_t s)
 {
-    const uint32_t buf_off[2] = {(uint32_t)kZeroBytes, (uint32_t)(kZeroBytes + L.act)};
+    const size_t buf_off[2] = {kZeroBytes, kZeroBytes + L.act};
+    uint8_t *seam = base + kZeroBytes + 2 * L.act + L.partial + 2 * L.stats;
     bf16_t *buf[2] = {(bf16_t *)(base + buf_off[0]), (bf16_t *)(base + buf_off[1])};
     float *partial = (float *)(base + kZeroBytes + 2 * L.act);
     float *tb[2] = {(float *)(base + kZeroBytes + 2 * L.act + L.partial),
@@ -390,19 +406,19 @@ qrm_status run_extractor(qrm_ctx *c, uint8_t *base, const WsLayout &L, TileSrc s
         src.off = off0 ? off0 + 2 * n0 : nullptr;
         int cur = 0, tcur = 0, in_slots = pf.slots * pf.sub;
         const int blocks = n_run > 0 ? n_run : c->n_blocks; // blocks to run: the first one and C -> C layers m = b - 1
-        // Fused schedule when the tile is a single column block: [first + layer 0], (1,2), (3,4), ..; what is
-        // left over runs alone.
-        const bool fused = !(c->diag_flags & QRM_DIAG_NO_FUSED_PAIRS) && c->pairable && conv_pair_supported(c->C, g) && blocks >= 2;
+        // Fused schedule (64 channels; see use_fused): [first + layer 0], (1,2), (3,4), ..; what is left over
+        // runs alone.
+        const bool fused = use_fused(c, cnt, w, blocks) && conv_pair_supported(c->C, g);
         auto is_last = [&](int b) { return n_run < 0 && c->collapse && b == c->n_blocks - 1; };
         int b = 1;
         if (fused) {
             qrm_ctx::Timed *t = time_begin(c, may_time, is_last(1) ? QRM_PROFILE_PAIR_LAST : QRM_PROFILE_PAIR_FIRST,
                                            (first_flops + block_flops) * cnt, s);
-            e = launch_conv_pair(base, 0, &src, g, c->C, c->d_w_first, c->d_w_mid[0], c->d_bias, c->d_bias + (size_t)c->C, nullptr,
-                                 0, nullptr, tb[tcur], is_last(1), c->num_cu, buf[cur], s);
+            e = launch_conv_pair(base, nullptr, &src, g, c->C, c->d_w_first, c->d_w_mid[0], c->d_bias, c->d_bias + (size_t)c->C, nullptr,
+                                 0, nullptr, tb[tcur], is_last(1), c->num_cu, seam, buf[cur], s);
             if (e != hipSuccess) return hip_fail(c, e, "conv_pair (first) launch");
             time_end(t, s);
-            in_slots = conv_pair_records_per_image();
+            in_slots = conv_pair_records_per_image(g, is_last(1));
             b = 2;
         } else {
             qrm_ctx::Timed *t = time_begin(c, may_time, QRM_PROFILE_BLOCK_FIRST, first_flops * cnt, s);
@@ -417,12 +433,12 @@ qrm_status run_extractor(qrm_ctx *c, uint8_t *base, const WsLayout &L, TileSrc s
             if (pair) {
                 qrm_ctx::Timed *t = time_begin(c, may_time, is_last(b + 1) ? QRM_PROFILE_PAIR_LAST : QRM_PROFILE_PAIR_MID,
                                                2.0 * block_flops * cnt, s);
-                e = launch_conv_pair(base, buf_off[cur], nullptr, g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1],
+                e = launch_conv_pair(base, base + buf_off[cur], nullptr, g, c->C, c->d_w_mid[m], c->d_w_mid[m + 1],
                                      c->d_bias + (size_t)b * c->C, c->d_bias + (size_t)(b + 1) * c->C, tb[tcur], in_slots, rsum,
-                                     tb[tcur ^ 1], is_last(b + 1), c->num_cu, buf[cur ^ 1], s);
+                                     tb[tcur ^ 1], is_last(b + 1), c->num_cu, seam, buf[cur ^ 1], s);
                 if (e != hipSuccess) return hip_fail(c, e, "conv_pair launch");
                 time_end(t, s);
-                in_slots = conv_pair_records_per_image();
+                in_slots = conv_pair_records_per_image(g, is_last(b + 1));
             } else {
                 qrm_ctx::Timed *t = time_begin(c, may_time, is_last(b) ? QRM_PROFILE_BLOCK_LAST : QRM_PROFILE_BLOCK_MID,
                                                block_flops * cnt, s);
@@ -548,7 +564,7 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         pack_first(w, ext->scale, C, frag);
         w += (size_t)C * 3 * 9;
         c->collapse = nb >= 2 && !c->final_relu;
-        // Fused schedule (launch_conv_pair; C = 64, tiles of one column block): [first block + C -> C layer 0],
+        // Fused schedule (launch_conv_pair; C = 64): [first block + C -> C layer 0],
         // then C -> C layers (1,2), (3,4), ..; a layer left over runs alone.  The second block of a fused
         // launch - the even C -> C layers - cannot have its bias corrected with channel means of its input
         // (that input never exists as a whole image): those layers get residual-cancelling rounding instead.

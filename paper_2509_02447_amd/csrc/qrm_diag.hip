@@ -53,7 +53,7 @@ extern "C" {
 qrm_status qrm_diag_set_flags(qrm_ctx *c, int32_t flags)
 {
     if (!c) return QRM_E_INVALID;
-    if (flags & ~(QRM_DIAG_NO_FUSED_PAIRS | QRM_DIAG_POISON_WORKSPACE | 0xFF00)) return fail(c, QRM_E_INVALID, "unknown diagnostic flag");
+    if (flags & ~(QRM_DIAG_NO_FUSED_PAIRS | QRM_DIAG_POISON_WORKSPACE | QRM_DIAG_FUSE_ALWAYS | 0xFF00)) return fail(c, QRM_E_INVALID, "unknown diagnostic flag");
     c->diag_flags = flags;
     return QRM_OK;
 }

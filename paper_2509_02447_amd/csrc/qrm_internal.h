@@ -57,30 +57,32 @@ size_t stat_record_floats(int C, int nq); // floats per statistics record holdin
 hipError_t launch_conv_first(const TileSrc &src, const ConvGeom &g, int C, const bf16_t *wfrag, const float *bias,
                              float *tout, const Partition &part, bf16_t *out, hipStream_t s);
 
-// conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out.  The input is addressed as ws + in_off (+ 32-bit
-// offsets); the first kZeroBytes of ws must be zero: they are the source of the zero padding.
+// conv3x3 C -> C + bias + ReLU, bf16 NHWC in/out.  The input is addressed as ws + in_off + image * its bytes
+// (+ 32-bit offsets inside an image); the first kZeroBytes of ws must be zero: the source of the zero padding.
 // tin / in_slots / rsum: channel sums of the input (in_slots records per image) and the summed weight-rounding
 // residual [c_in][c_out] used
 // to correct the bias (either may be null).  tout: statistics of the output.  last: no activations are
 // written, tout receives the nine border-aware sums per channel (stat_record_floats(C,9) per record).
 constexpr size_t kZeroBytes = 256;
-hipError_t launch_conv_mid(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
+hipError_t launch_conv_mid(const uint8_t *ws, size_t in_off, const ConvGeom &g, int C, const bf16_t *wfrag,
                            const float *bias, const float *tin, int in_slots, const float *rsum, float *tout,
                            const Partition &part, bool last, bf16_t *out, hipStream_t s);
 
-// Two consecutive blocks in one launch, the activations between them staying in LDS (tiles of one column
-// block, C = 64: conv_pair_supported).  first != nullptr: the first of the two is the network's first block
-// (raw u8 tiles, wfrag_a / bias_a of that block; ws / in_off / tin / rsum_a unused); otherwise both are
-// C -> C blocks and tin / in_slots / rsum_a are as for launch_conv_mid (first block only: the second block's
-// weights are rounded so that it needs no correction).  last: the second block is the network's last one
-// (no activations written, nine sums per channel in the records).  tout: channel sums of the output,
-// conv_pair_records_per_image() records per image.
+// Two consecutive blocks in one launch, the activations between them staying in LDS (C = 64:
+// conv_pair_supported; tiles wider than 64 columns are walked through in column blocks and need `seam`,
+// conv_pair_seam_bytes() bytes of scratch).  zeros: kZeroBytes of zeros; in: the input activations.
+// first != nullptr: the first of the two is the network's first block (raw u8 tiles, wfrag_a / bias_a of that
+// block; in / tin / rsum_a unused); otherwise both are C -> C blocks and tin / in_slots / rsum_a are as for
+// launch_conv_mid (first block only: the second block's weights are rounded so that it needs no correction).
+// last: the second block is the network's last one (no activations written, nine sums per channel in the
+// records).  tout: channel sums of the output, conv_pair_records_per_image() records per image.
 bool conv_pair_supported(int C, const ConvGeom &g);
-int conv_pair_records_per_image();
-hipError_t launch_conv_pair(const uint8_t *ws, uint32_t in_off, const TileSrc *first, const ConvGeom &g, int C,
+int conv_pair_records_per_image(const ConvGeom &g, bool last);
+size_t conv_pair_seam_bytes(const ConvGeom &g, int num_cu);
+hipError_t launch_conv_pair(const uint8_t *zeros, const uint8_t *in, const TileSrc *first, const ConvGeom &g, int C,
                             const bf16_t *wfrag_a, const bf16_t *wfrag_b, const float *bias_a, const float *bias_b,
                             const float *tin, int in_slots, const float *rsum_a, float *tout, bool last, int num_cu,
-                            bf16_t *out, hipStream_t s);
+                            uint8_t *seam, bf16_t *out, hipStream_t s);
 
 // nine channel sums of the last block -> final conv + average pool in closed form -> linear -> logits,
 // bits, symbols.  wft: final conv weights fp32, [C*9][nbp] (k = c*9 + tap major)
@@ -90,7 +92,7 @@ hipError_t launch_head(const float *recs, int slots, int C, int64_t n_img, int n
 
 // final conv3x3 C -> nbp (n_bits padded to 32s) (+bias, optional ReLU) + sum over pixels -> partial sums
 // partial: f32 [n_img][colblks*2][nbp]
-hipError_t launch_conv_final(const uint8_t *ws, uint32_t in_off, const ConvGeom &g, int C, int nbp,
+hipError_t launch_conv_final(const uint8_t *ws, size_t in_off, const ConvGeom &g, int C, int nbp,
                              const bf16_t *wfrag, const float *bias, int relu, float *partial, int num_cu,
                              hipStream_t s);
 

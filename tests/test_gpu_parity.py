@@ -279,6 +279,72 @@ def test_extractor_stream_of_images_per_workgroup(qrm, name, nb, nbits, h, w, N)
     ctx.close()
 
 
+WIDE_CASES = [   # name, blocks, bits, h, w, images, micro-batch: tiles wider than 64 columns on the fused kernels
+    ("C4 shape 128x128 b8 96bit", 8, 96, 128, 128, 2, 0),
+    ("two blocks 10x128 (first + last fused)", 2, 16, 10, 128, 3, 0),
+    ("ragged 20x130 b5", 5, 48, 20, 130, 3, 2),
+    ("three column blocks 7x192 b4", 4, 48, 7, 192, 2, 0),
+    ("one column over 33x65 b6", 6, 32, 33, 65, 3, 0),
+    ("four column blocks 3x256 b3", 3, 16, 3, 256, 2, 0),
+    ("ragged 40x100 b8", 8, 48, 40, 100, 2, 0),
+    ("one row 1x128 b4", 4, 16, 1, 128, 5, 0),
+    ("two images per workgroup 4x128 b4, 300 images", 4, 24, 4, 128, 300, 0),
+    ("three images per workgroup 6x70 b5, 520 images in micro-batches of 300", 5, 24, 6, 70, 520, 300),
+]
+
+
+@pytest.mark.parametrize("name,nb,nbits,h,w,N,mb", WIDE_CASES, ids=[c[0] for c in WIDE_CASES])
+def test_extractor_wide_tiles_on_fused_kernels(qrm, name, nb, nbits, h, w, N, mb):
+    """Tiles of more than one column block through the fused kernels (a workgroup walks through its image column
+    block by column block; the columns at the seams travel through a small buffer in global memory, and the last
+    column of a width that is a multiple of 64 comes from a launch of its own), forced on also where a launch has
+    too few images for that schedule to be chosen.  Against the oracle; twice, for equal bytes."""
+    wts = small_weights(64, nb, nbits, nb * 3 + nbits + w)
+    rng = np.random.default_rng(nbits + h + w)
+    tiles = rng.integers(0, 256, size=(N, 3, h, w), dtype=np.uint8)
+    keep = np.arange(N) if N <= 8 else np.unique(np.concatenate([np.arange(4), np.arange(N - 4, N), rng.integers(0, N, 24)]))
+    ref_logits, _ = oracle.extractor_forward(wts, tiles[keep])
+    ctx = qrm.Context(weights=wts)
+    ctx.qrm_diag_set_flags(qrm.binding.QRM_DIAG_FUSE_ALWAYS | qrm.binding.QRM_DIAG_POISON_WORKSPACE)
+    ctx.qrm_set_micro_batch(mb)
+    runs = []
+    for rep in range(2):
+        d_logits, d_bits = empty((N, nbits), torch.float32), empty((N, nbits), torch.uint8)
+        ctx.qrm_extractor_forward(dev(tiles), N, h, w, d_logits, d_bits)
+        torch.cuda.synchronize()
+        runs.append((d_logits.cpu().numpy(), d_bits.cpu().numpy()))
+    check_logits(runs[0][0][keep], ref_logits, runs[0][1][keep], what=name)
+    assert np.isfinite(runs[0][0]).all()
+    assert np.array_equal(runs[0][0], runs[1][0]) and np.array_equal(runs[0][1], runs[1][1])
+    ctx.close()
+
+
+@pytest.mark.parametrize("nb,h,w", [(2, 6, 128), (3, 5, 130), (4, 9, 192), (5, 4, 65)])
+def test_extractor_wide_tiles_layer_by_layer(qrm, nb, h, w):
+    """The activations themselves (not only their pooled sums) of wide tiles on the fused kernels, every pixel and
+    channel against the oracle: a wrong seam column or a missing last column is an O(1) error in single pixels
+    that global average pooling would hide."""
+    wts = small_weights(64, nb, 16, 64 + nb + w)
+    rng = np.random.default_rng(h * w)
+    tiles = rng.integers(0, 256, size=(2, 3, h, w), dtype=np.uint8)
+    ctx = qrm.Context(weights=wts)
+    ctx.qrm_diag_set_flags(qrm.binding.QRM_DIAG_FUSE_ALWAYS)
+    refs = [oracle.extractor_forward(wts, tiles[i:i + 1], want_acts=True)[2] for i in range(2)]
+    for b in range(1, nb + 1):
+        d_act = empty((2, 64, h, w), torch.float32)
+        ctx.qrm_extractor_blocks(dev(tiles), 2, h, w, b, d_act)
+        torch.cuda.synchronize()
+        got = d_act.cpu().numpy().astype(np.float64)
+        for i in range(2):
+            ref = refs[i][b - 1]
+            err = np.abs(got[i] - ref) / np.maximum(1.0, np.abs(ref))
+            rms = float(np.sqrt(np.mean((got[i] - ref) ** 2)))
+            print(f"[parity] wide {h}x{w} block {b} image {i}: max scaled activation error {err.max():.3e}, rms {rms:.3e}")
+            assert err.max() <= 0.05 and rms <= 0.004 * b + 0.006, (b, i, float(err.max()), rms,
+                                                                     np.unravel_index(err.argmax(), err.shape))
+    ctx.close()
+
+
 def test_extractor_final_relu_and_affine(qrm):
     wts = small_weights(64, 2, 48, 99)
     g = np.random.default_rng(9)
