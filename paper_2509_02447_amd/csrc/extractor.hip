@@ -77,29 +77,44 @@ __device__ __forceinline__ int pin_in_loop(int v)
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-// two fp32 -> packed bf16 (round to nearest even) with ReLU applied on the packed pair: a negative bf16
-// has its sign bit set, i.e. is negative as a 16-bit integer, so max(.,0) on the halves clamps it.
-// The operands must not be the result registers of a matrix instruction: the compiler puts the wait states a
-// matrix result needs in front of its own instructions only, not in front of an asm statement, which would
-// then now and then read the registers before the last matrix instruction has written them (seen as
-// run-to-run differences of one bf16 step).  Every caller adds the bias first.
-__device__ __forceinline__ uint32_t pack_bf16_relu(float a, float b, bool relu)
+// Activations are rounded to bf16 once per layer.  Round-to-nearest makes the same error wherever the value
+// is the same: on a flat or smooth image every pixel of a channel is off in the same direction, and that part
+// of the error survives the global average pool (measured: up to 3.4e-2 of a logit on one-colour images,
+// against 2e-3 on noise).  The rounding is therefore dithered by position: a pixel adds a fraction u(x, y) of a
+// bf16 step to the value's bits and truncates, u in [0, 1) a fixed pseudo-random function of the pixel's place
+// in the tile (an integer hash: an ordered pattern would line up with regular image content such as a
+// checkerboard).  Single values are off by up to one step instead of half a step; sums over pixels, which is
+// all the method looks at, come out unbiased.  Deterministic: the same pixel always gets the same u.
+__device__ __forceinline__ uint32_t dither16(int x, int y)
 {
-    uint32_t p; // (the compiler would convert the two halves separately and merge them with a permute)
-    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(p) : "v"(a), "v"(b));
+    uint32_t h = (uint32_t)x * 0x9E3779B1u + (uint32_t)y * 0x85EBCA77u;
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    h ^= h >> 13;
+    return h & 0xffffu;
+}
+
+// two fp32 -> packed bf16, each truncated after `dither` (< 2^16) has been added to its bits, with ReLU
+// applied on the packed pair: a negative bf16 has its sign bit set, i.e. is negative as a 16-bit integer, so
+// max(.,0) on the halves clamps it.  (Plain instructions: the compiler puts the wait states a matrix result
+// needs in front of its own instructions only, never in front of an asm statement.)
+__device__ __forceinline__ uint32_t pack_bf16_relu(float a, float b, uint32_t dither, bool relu)
+{
+    const uint32_t ua = __builtin_bit_cast(uint32_t, a) + dither, ub = __builtin_bit_cast(uint32_t, b) + dither;
+    const uint32_t p = __builtin_amdgcn_perm(ub, ua, 0x07060302u); // the high halves: a's below b's
     s16x2 q = __builtin_bit_cast(s16x2, p);
     if (relu) q = __builtin_elementwise_max(q, (s16x2){0, 0});
     return __builtin_bit_cast(uint32_t, q);
 }
 
 // lane (px, half) holds 16 consecutive channels [half*16, half*16+16) of the 32-channel block
-__device__ __forceinline__ void store_tile_bf16(bf16_t *dst, const f32x16 &acc, bool relu)
+__device__ __forceinline__ void store_tile_bf16(bf16_t *dst, const f32x16 &acc, uint32_t dither, bool relu)
 {
     u32x4 lo, hi;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
-        lo[v] = pack_bf16_relu(acc[2 * v], acc[2 * v + 1], relu);
-        hi[v] = pack_bf16_relu(acc[8 + 2 * v], acc[8 + 2 * v + 1], relu);
+        lo[v] = pack_bf16_relu(acc[2 * v], acc[2 * v + 1], dither, relu);
+        hi[v] = pack_bf16_relu(acc[8 + 2 * v], acc[8 + 2 * v + 1], dither, relu);
     }
     *(u32x4 *)dst = lo;
     *(u32x4 *)(dst + 8) = hi;
@@ -562,11 +577,12 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
                 const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                 for (int r = 0; r < RW; ++r) {
+                    const uint32_t dth = dither16(x, yw + r);
                     u32x4 pk;
-                    pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
-                    pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
-                    pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
-                    pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                    pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], dth, true);
+                    pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], dth, true);
+                    pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], dth, true);
+                    pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], dth, true);
                     bf16_t *dst = out_img + (e0 + (uint32_t)(r * g.w * C) + 8 * hq);
                     if (full) *(u32x4 *)dst = pk;
                     else if (yw + r < g.h && x < g.w) *(u32x4 *)dst = pk;
@@ -718,7 +734,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     constexpr int PIECES = (SLOTS + 63) / 64;     // wavefront-wide loads per row, the last one partial
     __shared__ __attribute__((aligned(1024))) uint8_t ring_in[FIRST ? 1024 : kPairRing * ROWB];
     __shared__ __attribute__((aligned(16))) uint8_t ring_mid[kPairRing * ROWB];
-    __shared__ __attribute__((aligned(16))) uint16_t s_pix[FIRST ? kPairRing : 1][kHaloW][4]; // normalised bf16 pixels, channel 3 = 0
+    __shared__ __attribute__((aligned(16))) uint16_t s_pix[FIRST ? kPairRing : 1][kHaloW][4]; // raw pixels as bf16; channel 3 = 1 inside the tile
     __shared__ __attribute__((aligned(16))) float s_initA[C]; // first block: bias (+ rounding-residual correction of the image)
     __shared__ __attribute__((aligned(16))) float s_biasB[C];
     __shared__ __attribute__((aligned(16))) float s_stat[4][NQ][32];
@@ -821,8 +837,6 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
     // FIRST: rows of the raw tile -> normalised bf16 pixels in s_pix, by the 256 threads of group A.
     // Element e of a row pair: row e / 198, channel (e % 198) / 66, staged column (e % 198) % 66.
     constexpr int kRowElems = 3 * kHaloW;
-    const float ka[3] = {src.inv_std[0] * (1.0f / 255.0f), src.inv_std[1] * (1.0f / 255.0f), src.inv_std[2] * (1.0f / 255.0f)};
-    const float kb[3] = {-src.mean[0] * src.inv_std[0], -src.mean[1] * src.inv_std[1], -src.mean[2] * src.inv_std[2]};
     const int plane = src.H * src.W;
     // The load is unconditional (coordinates clamped into the tile, the value dropped later when it lies
     // outside) and fetches the aligned dword that holds the byte (it never leaves the byte's page): a load under
@@ -845,10 +859,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         if (e < 2 * kRowElems) {
             const int row = e / kRowElems, rem = e - row * kRowElems;
             const int c = rem / kHaloW, col = rem - c * kHaloW;
-            const float a = c == 0 ? ka[0] : (c == 1 ? ka[1] : ka[2]);
-            const float b = c == 0 ? kb[0] : (c == 1 ? kb[1] : kb[2]);
-            const float f = inside ? fmaf((float)((word >> shift) & 0xffu), a, b) : 0.f;
+            // the byte itself, exact as bf16: the normalisation lives in the weights (see conv_first_kernel)
+            const float f = inside ? (float)((word >> shift) & 0xffu) : 0.f;
             s_pix[slot_of(y0 + row)][col][c] = __builtin_bit_cast(uint16_t, (bf16_t)f);
+            if (c == 0) s_pix[slot_of(y0 + row)][col][3] = inside ? (uint16_t)0x3F80 : (uint16_t)0; // 1 inside the tile
         }
     };
 
@@ -864,7 +878,6 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         if (tid - 256 < C) s_biasB[tid - 256] = biasB[tid - 256];
     } else if (FIRST) {
         if (tid < C) s_initA[tid] = biasA[tid];
-        for (int i = tid; i < kPairRing * kHaloW; i += 256) s_pix[i / kHaloW][i % kHaloW][3] = 0; // the padding channel
     }
     if (!WIDE) // (WIDE: pixels 0 and 1 are rewritten in every step, 2 .. 65 by group A)
     for (int i = tid; i < kPairRing * 2 * (K::PS / 16); i += 512) { // columns -1 and w.. stay zero for good
@@ -959,11 +972,12 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
+                        const uint32_t dth = dither16(x, 2 * j + r);
                         u32x4 pk;
-                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
-                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
-                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
-                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], dth, true);
+                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], dth, true);
+                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], dth, true);
+                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], dth, true);
                         *(u32x4 *)(rows + (le + r * rstride + 8 * hq)) = pk;
                     }
                 }
@@ -973,11 +987,12 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
+                        const uint32_t dth = dither16(x, 2 * j + r);
                         u32x4 pk;
-                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], true);
-                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], true);
-                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], true);
-                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], true);
+                        pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], dth, true);
+                        pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], dth, true);
+                        pk[2] = pack_bf16_relu(a[r][8 * hq + 4] + b1[0], a[r][8 * hq + 5] + b1[1], dth, true);
+                        pk[3] = pack_bf16_relu(a[r][8 * hq + 6] + b1[2], a[r][8 * hq + 7] + b1[3], dth, true);
                         if (2 * j + r < g.h && (uint32_t)x < (uint32_t)g.w) *(u32x4 *)(rows + (le + r * rstride + 8 * hq)) = pk;
                     }
                 }
@@ -1093,11 +1108,12 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
                         const int y = 2 * pa.s + r;
+                        const uint32_t dth = dither16(x, y);
                         u32x4 pk;
-                        pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], true);
-                        pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], true);
-                        pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], true);
-                        pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], true);
+                        pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], dth, true);
+                        pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], dth, true);
+                        pk[2] = pack_bf16_relu(acc[r][8 * hq + 4] + b1[0], acc[r][8 * hq + 5] + b1[1], dth, true);
+                        pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], dth, true);
                         if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
                         *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + kSkew + xl) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
                         if (WIDE && seam_rows && xl >= kTileW - 2)
@@ -1228,7 +1244,7 @@ __global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restric
             }
     }
     const float *bp = biasB + cb * 32 + half * 16;
-    float val[16]; // bias added by ordinary vector instructions (see pack_bf16_relu)
+    float val[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) val[v] = sum[v] + bp[v];
     if (!LASTB) {
@@ -1237,8 +1253,8 @@ __global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restric
             u32x4 lo, hi;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                lo[v] = pack_bf16_relu(val[2 * v], val[2 * v + 1], true);
-                hi[v] = pack_bf16_relu(val[8 + 2 * v], val[8 + 2 * v + 1], true);
+                lo[v] = pack_bf16_relu(val[2 * v], val[2 * v + 1], dither16(g.w - 1, r), true);
+                hi[v] = pack_bf16_relu(val[8 + 2 * v], val[8 + 2 * v + 1], dither16(g.w - 1, r), true);
             }
             *(u32x4 *)dst = lo;
             *(u32x4 *)(dst + 8) = hi;
@@ -1366,10 +1382,14 @@ __global__ __launch_bounds__(256, 2) void conv_final_kernel(const uint8_t *__res
 
 // ------------------------------------------------------------------------------------------------
 // First layer: u8 planes -> crop -> normalise -> conv3x3 (3 -> C) + bias + ReLU -> bf16 NHWC.
-// A workgroup stages the (4+2) x (64+2) window of the tile as normalised bf16 pixels of 4 channels
-// (r, g, b, 0 = 8 bytes) in LDS; whatever lies outside the tile is a literal zero, i.e. zero padding in
-// the normalised domain.  K = 9 taps x 4 channels = 36, padded to 48 = three 16-wide k chunks; a lane's
-// 8 k values of a chunk are two taps, i.e. two 8-byte LDS reads.  A wavefront computes one 32-channel
+// The normalisation is folded into the weights, so that the operands of the matrix cores are exact:
+//   sum_c w[c] * (p_c / 255 - mean_c) / std_c  =  sum_c (w[c] / (255 std_c)) * p_c  +  (- sum_c w[c] mean_c / std_c) * 1
+// A workgroup stages the (4+2) x (64+2) window of the tile as pixels of 4 bf16 channels (8 bytes) in LDS: the
+// three bytes as they are (0..255 are exact in bf16) and a fourth channel that is 1 inside the tile; whatever
+// lies outside the tile is four zeros, which is the zero padding of the normalised domain exactly (the
+// constant term vanishes with the indicator).  The weights of the four channels are kept as bf16 high part +
+// bf16 residual, i.e. to about 16 bits.  K = 9 taps x 4 channels = 36, padded to 48 = three 16-wide k chunks;
+// a lane's 8 k values of a chunk are two taps, i.e. two 8-byte LDS reads.  A wavefront computes one 32-channel
 // output block for one (C = 32) or two (C = 64) rows of the strip.
 // ------------------------------------------------------------------------------------------------
 constexpr int kFirstPix = (kRows + 2) * kHaloW;
@@ -1417,14 +1437,10 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
             tap = tap > 8 ? 8 : tap;
             toff[q][j] = ((tap / 3) * kHaloW + tap % 3) * 8;
         }
-    for (int i = tid; i < kFirstPix; i += 256) lds[i * 4 + 3] = 0; // the padding channel stays zero
     for (int i = tid; i < 4 * 32; i += 256) (&s_stat[0][0])[i] = 0.f;
     if (tid < 4) s_cnt[tid] = 0.f;
 
     const int plane = src.H * src.W;
-    const float ka[3] = {src.inv_std[0] * (1.0f / 255.0f), src.inv_std[1] * (1.0f / 255.0f),
-                         src.inv_std[2] * (1.0f / 255.0f)};
-    const float kb[3] = {-src.mean[0] * src.inv_std[0], -src.mean[1] * src.inv_std[1], -src.mean[2] * src.inv_std[2]};
 
     const int tpi = g.strips * g.colblks;
     const int total = g.n_img * tpi;
@@ -1474,13 +1490,11 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
                 const int c = idx / kFirstPix, p = idx - c * kFirstPix;
                 const int row = p / kHaloW, col = p - row * kHaloW;
                 const int ty = y0 - 1 + row, tx = x0 - 1 + col;
+                const bool inside = ty >= 0 && ty < g.h && tx >= 0 && tx < g.w;
                 float v = 0.f;
-                if (ty >= 0 && ty < g.h && tx >= 0 && tx < g.w) {
-                    const float a = c == 0 ? ka[0] : (c == 1 ? ka[1] : ka[2]);
-                    const float b = c == 0 ? kb[0] : (c == 1 ? kb[1] : kb[2]);
-                    v = fmaf((float)tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx], a, b);
-                }
+                if (inside) v = (float)tile0[(int64_t)c * plane + (int64_t)ty * src.W + tx];
                 lds[p * 4 + c] = __builtin_bit_cast(uint16_t, (bf16_t)v);
+                if (c == 0) lds[p * 4 + 3] = inside ? (uint16_t)0x3F80 : (uint16_t)0;
             }
         }
         __syncthreads();
@@ -1510,12 +1524,11 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
                 sum = mfma32(Wr[0][2], bfrag[2], sum);
 #pragma unroll
                 for (int q = 0; q < 3; ++q) sum = mfma32(Wr[1][q], bfrag[q], sum);
-                // the bias is added by ordinary vector instructions: see pack_bf16_relu
                 f32x16 acc;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[v] = sum[v] + bias16[v];
                 if (x < g.w)
-                    store_tile_bf16(out + (((int64_t)n * g.h + y) * g.w + x) * C + cb * 32 + half * 16, acc, true);
+                    store_tile_bf16(out + (((int64_t)n * g.h + y) * g.w + x) * C + cb * 32 + half * 16, acc, dither16(x, y), true);
                 if (sample) {
                     float tv[16];
 #pragma unroll

@@ -131,24 +131,35 @@ float bf16_to_f32(uint16_t h)
     return f;
 }
 
-// bf16 values of one layer's (scaled) weights, [o][ci][tap].  diffuse = false: each weight rounded to
-// nearest even.  diffuse = true: error feedback over the nine taps of every (o, ci) pair - each tap is
-// rounded after the residual of the taps before it has been added - so that the residuals of the nine
-// taps sum to (almost) nothing: the part of the rounding error that acts on the mean activation, the
-// only part that global average pooling does not wash out, is gone without any correction term.
-std::vector<uint16_t> round_layer(const float *w, const float *scale, int cout, int cin, bool diffuse)
+// bf16 values of one layer's (scaled) weights, [o][ci][tap].  cancel = false: each weight rounded to nearest
+// even.  cancel = true: error feedback over the taps of every (o, ci) pair - each tap is rounded after the
+// residual of the taps before it has been added - so that the residuals sum to (almost) nothing: the part of
+// the rounding error that acts on the mean activation, the only part that global average pooling does not
+// wash out, is gone without any correction term.  Two refinements, both measured on structured tiles: the
+// taps are taken largest first, so that what is left over at the end is a fraction of the smallest weight's
+// rounding step, not of a typical one; and the taps with dy + dx even and those with dy + dx odd form two
+// chains of their own, so that the residuals also cancel against an activation map that alternates from
+// pixel to pixel (a one-pixel checkerboard keeps that structure through every layer).
+std::vector<uint16_t> round_layer(const float *w, const float *scale, int cout, int cin, bool cancel)
 {
     std::vector<uint16_t> r((size_t)cout * cin * 9);
     for (int o = 0; o < cout; ++o)
         for (int ci = 0; ci < cin; ++ci) {
-            double carry = 0.0;
+            const size_t base = ((size_t)o * cin + ci) * 9;
+            float v[9];
+            int order[9];
             for (int tap = 0; tap < 9; ++tap) {
-                const size_t i = ((size_t)o * cin + ci) * 9 + tap;
-                const float v = w[i] * (scale ? scale[o] : 1.f);
-                const float target = diffuse ? (float)((double)v + carry) : v;
-                r[i] = f32_to_bf16_rne(target);
-                carry = (double)v + carry - (double)bf16_to_f32(r[i]);
-                if (!diffuse) carry = 0.0;
+                v[tap] = w[base + tap] * (scale ? scale[o] : 1.f);
+                order[tap] = tap;
+            }
+            if (cancel) std::stable_sort(order, order + 9, [&](int a, int b) { return fabsf(v[a]) > fabsf(v[b]); });
+            double carry[2] = {0.0, 0.0};
+            for (int k = 0; k < 9; ++k) {
+                const int tap = order[k];
+                const int chain = (tap / 3 + tap % 3) & 1;
+                const float target = cancel ? (float)((double)v[tap] + carry[chain]) : v[tap];
+                r[base + tap] = f32_to_bf16_rne(target);
+                carry[chain] += (double)v[tap] - (double)bf16_to_f32(r[base + tap]);
             }
         }
     return r;
@@ -168,9 +179,12 @@ void pack_mid(const std::vector<uint16_t> &r, int cout, int cout_pad, int cin, s
                     }
 }
 
-// first layer: k = q*16 + (lane/32)*8 + e  ->  tap = k/4 (0..8, beyond: zero), channel = k%4 (3: zero).
-// Per output block two fragment sets: bf16(w) and bf16(w - bf16(w)).
-void pack_first(const float *w, const float *scale, int cout, std::vector<uint16_t> &dst)
+// first layer: k = q*16 + (lane/32)*8 + e  ->  tap = k/4 (0..8, beyond: zero), channel = k%4.
+// The kernels feed the raw bytes p_c (exact in bf16) and a fourth channel that is 1 inside the tile, so the
+// normalisation x_c = (p_c / 255 - mean_c) / std_c is folded into the weights: channel c < 3 carries
+// w / (255 std_c), channel 3 carries - sum_c w mean_c / std_c (per tap).
+// Per output block two fragment sets: bf16(v) and bf16(v - bf16(v)).
+void pack_first(const float *w, const float *scale, int cout, const float *mean, const float *std, std::vector<uint16_t> &dst)
 {
     for (int blk = 0; blk < cout / 32; ++blk)
         for (int part = 0; part < 2; ++part)
@@ -180,10 +194,16 @@ void pack_first(const float *w, const float *scale, int cout, std::vector<uint16
                         const int o = blk * 32 + perm32(lane & 31);
                         const int k = q * 16 + (lane >> 5) * 8 + e;
                         const int tap = k / 4, ch = k % 4;
-                        float v = 0.f;
-                        if (tap < 9 && ch < 3) v = w[((size_t)o * 3 + ch) * 9 + tap] * (scale ? scale[o] : 1.f);
-                        const uint16_t hi = f32_to_bf16_rne(v);
-                        dst.push_back(part == 0 ? hi : f32_to_bf16_rne(v - bf16_to_f32(hi)));
+                        double v = 0.0;
+                        if (tap < 9) {
+                            const double sc = scale ? (double)scale[o] : 1.0;
+                            if (ch < 3) v = (double)w[((size_t)o * 3 + ch) * 9 + tap] * sc / (255.0 * (double)std[ch]);
+                            else
+                                for (int c = 0; c < 3; ++c)
+                                    v -= (double)w[((size_t)o * 3 + c) * 9 + tap] * sc * (double)mean[c] / (double)std[c];
+                        }
+                        const uint16_t hi = f32_to_bf16_rne((float)v);
+                        dst.push_back(part == 0 ? hi : f32_to_bf16_rne((float)(v - (double)bf16_to_f32(hi))));
                     }
 }
 
@@ -561,7 +581,7 @@ qrm_status qrm_create(const qrm_extractor_desc *ext, const qrm_rs_desc *rs, int 
         std::vector<size_t> frag_off; // element offsets: first, mids..., final
         const float *w = ext->conv_w;
         frag_off.push_back(frag.size());
-        pack_first(w, ext->scale, C, frag);
+        pack_first(w, ext->scale, C, ext->mean, ext->std, frag);
         w += (size_t)C * 3 * 9;
         c->collapse = nb >= 2 && !c->final_relu;
         // Fused schedule (launch_conv_pair; C = 64): [first block + C -> C layer 0],

@@ -200,11 +200,12 @@ def test_extractor_blocks_match_oracle_layer_by_layer(qrm, C, nb, h, w):
             ref = refs[i][b - 1]
             err = np.abs(got[i] - ref) / np.maximum(1.0, np.abs(ref))
             print(f"[parity] C={C} {h}x{w} block {b} image {i}: max scaled activation error {err.max():.3e}")
-            # bf16 operands (inputs and weights, relative step 2^-9 each) and one bf16 rounding per layer:
-            # an element of size ~1 built from 27..576 products carries noise of a few 1e-3; the maximum
-            # over ~1e5 elements sits near 2e-2.  A wrong tap, channel or halo is an O(1) error.
+            # bf16 operands (weights: relative step 2^-9) and one dithered bf16 rounding per layer (off by up to
+            # one step of 2^-8 relative, unbiased): an element of size ~1 built from 27..576 products carries noise
+            # of a few 1e-3; the maximum over ~1e5 elements sits near 3e-2.  A wrong tap, channel or halo is an
+            # O(1) error in single elements and shows in the rms.
             rms = float(np.sqrt(np.mean((got[i] - ref) ** 2)))
-            assert err.max() <= 0.05 and rms <= 0.004 * b + 0.006, (b, i, float(err.max()), rms,
+            assert err.max() <= 0.08 and rms <= 0.005 * b + 0.007, (b, i, float(err.max()), rms,
                                                                      np.unravel_index(err.argmax(), err.shape))
     ctx.close()
 
@@ -267,15 +268,11 @@ def test_extractor_stream_of_images_per_workgroup(qrm, name, nb, nbits, h, w, N)
         ctx.qrm_extractor_forward(dev(tiles), N, h, w, d_logits, d_bits)
         torch.cuda.synchronize()
         g, gb = d_logits.cpu().numpy(), d_bits.cpu().numpy()
-        rest = np.ones(N, dtype=bool)
-        rest[N // 2:N // 2 + 2] = False
-        check_logits(g[rest], ref_logits[rest], gb[rest], what=f"{name}, micro-batch {mb}")
-        # A constant image is the worst case of bf16 activations: every pixel of a channel carries the same
-        # value, so its rounding error (up to 2^-9 relative per block) is the same everywhere and survives the
-        # average pool instead of averaging out.  Measured up to 3.4e-2 (fused or not); bound kept apart.
-        flat = np.abs(g[~rest] - ref_logits[~rest]) / np.maximum(1.0, np.abs(ref_logits[~rest]))
-        print(f"[parity] {name}, micro-batch {mb}: constant images, max scaled logit error {flat.max():.3e} (limit 8e-2)")
-        assert flat.max() <= 8e-2
+        check_logits(g, ref_logits, gb, what=f"{name}, micro-batch {mb}")
+        # (a one-colour image is the hardest case for bf16 activations: every pixel of a channel carries the same
+        # value, so a rounding error that is the same everywhere survives the average pool: hence the dithered rounding)
+        flat = np.abs(g[N // 2:N // 2 + 2] - ref_logits[N // 2:N // 2 + 2]) / np.maximum(1.0, np.abs(ref_logits[N // 2:N // 2 + 2]))
+        print(f"[parity] {name}, micro-batch {mb}: the black and the white image, max scaled logit error {flat.max():.3e}")
     ctx.close()
 
 
@@ -342,6 +339,58 @@ def test_extractor_wide_tiles_layer_by_layer(qrm, nb, h, w):
             print(f"[parity] wide {h}x{w} block {b} image {i}: max scaled activation error {err.max():.3e}, rms {rms:.3e}")
             assert err.max() <= 0.05 and rms <= 0.004 * b + 0.006, (b, i, float(err.max()), rms,
                                                                      np.unravel_index(err.argmax(), err.shape))
+    ctx.close()
+
+
+def structured_tiles(h, w, seed):
+    """Tiles that are anything but stationary noise: one-colour, bands, ramps, halves, fine patterns."""
+    rng = np.random.default_rng(seed)
+    yy, xx = np.meshgrid(np.arange(h), np.arange(w), indexing="ij")
+    t = []
+    for level in (0, 255, 128, 1, 77):
+        t.append(np.full((3, h, w), level))
+    t.append(np.stack([np.full((h, w), v) for v in (200, 30, 111)]))                  # one level per channel
+    band = np.zeros((3, h, w)); band[:, :max(1, h // 8)] = 255; t.append(band)         # bright band at the top
+    band = np.full((3, h, w), 40); band[:, -max(1, h // 5):] = 230; t.append(band)     # and one at the bottom
+    t.append(np.broadcast_to(255.0 * yy / max(1, h - 1), (3, h, w)))                   # vertical ramp
+    t.append(np.broadcast_to(255.0 * xx / max(1, w - 1), (3, h, w)))                   # horizontal ramp
+    half = np.zeros((3, h, w)); half[:, :, w // 2:] = 255; t.append(half)              # left black, right white
+    half = np.zeros((3, h, w)); half[:, h // 2:] = 255; t.append(half)                 # top black, bottom white
+    t.append(np.broadcast_to(255.0 * ((yy + xx) & 1), (3, h, w)))                      # one-pixel checkerboard
+    t.append(np.broadcast_to(255.0 * (((yy >> 1) + (xx >> 1)) & 1), (3, h, w)))        # two-pixel checkerboard
+    t.append(np.broadcast_to(255.0 * ((xx & 3) == 0), (3, h, w)))                      # every fourth column
+    t.append(np.clip(128 + 20 * rng.standard_normal((3, h, w)), 0, 255))               # grey with a little noise
+    return np.stack([np.rint(np.asarray(a, dtype=np.float64)) for a in t]).astype(np.uint8)
+
+
+STRUCTURED_CASES = [   # name, channels, blocks, bits, h, w, diagnostic flags
+    ("64x64 c64 b8 fused", 64, 8, 48, 64, 64, 0),
+    ("64x64 c64 b8 single blocks", 64, 8, 48, 64, 64, 1),
+    ("32x32 c32 b4", 32, 4, 60, 32, 32, 0),
+    ("128x128 c64 b8 fused, wide", 64, 8, 96, 128, 128, 4),
+    ("128x128 c64 b8 single blocks", 64, 8, 96, 128, 128, 0),
+    ("40x100 c64 b5 fused, wide", 64, 5, 48, 40, 100, 4),
+]
+
+
+@pytest.mark.parametrize("name,C,nb,nbits,h,w,flags", STRUCTURED_CASES, ids=[c[0] for c in STRUCTURED_CASES])
+def test_extractor_structured_tiles(qrm, name, C, nb, nbits, h, w, flags):
+    """One-colour, banded, ramped, halved and finely patterned tiles (ordinary detector inputs, and the hard cases
+    of bf16 activations and of channel means estimated from sampled rows) at the tolerance of every other tile,
+    hard bits included, on the configurations' weights."""
+    wts = synth.extractor_weights(3, nb, C, nbits, seed_index={96: 3, 48: 1, 60: 0}[nbits])
+    tiles = structured_tiles(h, w, h + w)
+    N = tiles.shape[0]
+    ref_logits, _ = oracle.extractor_forward(wts, tiles)
+    ctx = qrm.Context(weights=wts)
+    ctx.qrm_diag_set_flags(flags)
+    d_logits, d_bits = empty((N, nbits), torch.float32), empty((N, nbits), torch.uint8)
+    ctx.qrm_extractor_forward(dev(tiles), N, h, w, d_logits, d_bits)
+    torch.cuda.synchronize()
+    g = d_logits.cpu().numpy()
+    err = (np.abs(g - ref_logits) / np.maximum(1.0, np.abs(ref_logits))).max(axis=1)
+    print(f"[parity] {name}: scaled logit error per tile " + " ".join(f"{e:.1e}" for e in err))
+    check_logits(g, ref_logits, d_bits.cpu().numpy(), what=name)
     ctx.close()
 
 
