@@ -85,13 +85,19 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 // in the tile (an integer hash: an ordered pattern would line up with regular image content such as a
 // checkerboard).  Single values are off by up to one step instead of half a step; sums over pixels, which is
 // all the method looks at, come out unbiased.  Deterministic: the same pixel always gets the same u.
+// One hash per group of rows a wavefront finishes together (the group's first row; the only full 32-bit multiply
+// is the column's share, the row's share is the same for the whole wavefront and lives on the scalar unit); the
+// other rows of the group take the same fraction shifted by a half or by quarters of a step, which spreads the
+// fractions of vertically neighbouring pixels evenly.
 __device__ __forceinline__ uint32_t dither16(int x, int y)
 {
+#ifdef QRM_EXP_NODITHER
+    return 0x8000u;
+#endif
     uint32_t h = (uint32_t)x * 0x9E3779B1u + (uint32_t)y * 0x85EBCA77u;
     h ^= h >> 15;
-    h *= 0x2C1B3C6Du;
-    h ^= h >> 13;
-    return h & 0xffffu;
+    h = __umul24(h, 0x00C1B3C5u); // low 24 bits x 24 bits: the product's upper half depends on all of them
+    return h >> 16;
 }
 
 // two fp32 -> packed bf16, each truncated after `dither` (< 2^16) has been added to its bits, with ReLU
@@ -570,6 +576,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
         if (MODE == MODE_MID) {
             // the image's activations (same for the whole workgroup) + element offset of this lane's first row
             bf16_t *out_img = out + (size_t)n * g.h * g.w * C;
+            const uint32_t dbase = dither16(x, yw);
             const uint32_t e0 = (uint32_t)((yw * g.w + x) * C + cb * 32 + half * 16);
             const bool full = y0 + kRows <= g.h && x0 + kTileW <= g.w; // same for the whole workgroup
 #pragma unroll
@@ -577,7 +584,7 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
                 const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                 for (int r = 0; r < RW; ++r) {
-                    const uint32_t dth = dither16(x, yw + r);
+                    const uint32_t dth = dbase ^ ((uint32_t)r << 14); // the strip's rows: quarter steps apart
                     u32x4 pk;
                     pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], dth, true);
                     pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], dth, true);
@@ -965,6 +972,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             bf16_t *rows = out + ((size_t)n * g.h + 2 * j) * ((size_t)g.w * C);
             const int le = x * C + cb * 32 + hf * 16;
             const int rstride = g.w * C;
+            const uint32_t dbase = dither16(x, 2 * j);
             const bool full = 2 * j + RW <= g.h && x_lo >= 0 && x_lo + kTileW <= g.w; // same for the whole workgroup
             if (full) { // the common case: straight-line code, no predicates
 #pragma unroll
@@ -972,7 +980,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
-                        const uint32_t dth = dither16(x, 2 * j + r);
+                        const uint32_t dth = dbase ^ ((uint32_t)r << 15); // the pair's second row: half a step apart
                         u32x4 pk;
                         pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], dth, true);
                         pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], dth, true);
@@ -987,7 +995,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     const f32x4 b0 = *(const f32x4 *)(si + 8 * hq), b1 = *(const f32x4 *)(si + 8 * hq + 4);
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
-                        const uint32_t dth = dither16(x, 2 * j + r);
+                        const uint32_t dth = dbase ^ ((uint32_t)r << 15); // the pair's second row: half a step apart
                         u32x4 pk;
                         pk[0] = pack_bf16_relu(a[r][8 * hq + 0] + b0[0], a[r][8 * hq + 1] + b0[1], dth, true);
                         pk[1] = pack_bf16_relu(a[r][8 * hq + 2] + b0[2], a[r][8 * hq + 3] + b0[3], dth, true);
@@ -1022,6 +1030,19 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         }
     };
 
+    // FIRST, group A: where in the pixel ring this lane's two taps of every k chunk lie (chunk k, half hf: taps
+    // 4k + 2hf and 4k + 2hf + 1; beyond 8: zero weights, tap 8 re-read): row offset dy and byte offset of
+    // column xl + dx, fixed for the lifetime of the workgroup
+    int tap_dy[3][2], tap_col8[3][2];
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+#pragma unroll
+        for (int j2 = 0; j2 < 2; ++j2) {
+            int tap = 4 * k + 2 * half + j2;
+            tap = tap > 8 ? 8 : tap;
+            tap_dy[k][j2] = tap / 3;
+            tap_col8[k][j2] = (xb * 32 + px + tap % 3) * 8;
+        }
     f32x16 acc[RW];
     const int n_steps = n_cnt * J * P + 2;
     const size_t seam_half = (size_t)(2 * S) * kSeamRowBytes; // one of a workgroup's two seam buffers
@@ -1058,21 +1079,15 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
                         const int vy = 2 * sg + r;
-                        const uint8_t *lp[3];
-#pragma unroll
-                        for (int dy = 0; dy < 3; ++dy) lp[dy] = (const uint8_t *)&s_pix[slot_of(vy - 1 + dy)][xb * 32 + pxl][0];
                         bf16x8 bfrag[3];
 #pragma unroll
-                        for (int k = 0; k < 3; ++k) { // k chunk: taps 4k + 2 hf and 4k + 2 hf + 1 (beyond 8: zero weights, tap 8 re-read)
+                        for (int k = 0; k < 3; ++k) {
                             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                             u32x2 two[2];
 #pragma unroll
                             for (int j2 = 0; j2 < 2; ++j2) {
-                                int tap = 4 * k + 2 * hf + j2;
-                                tap = tap > 8 ? 8 : tap;
-                                const int dy = tap / 3, dx = tap - dy * 3;
-                                const uint8_t *p0 = dy == 0 ? lp[0] : (dy == 1 ? lp[1] : lp[2]);
-                                two[j2] = *(const u32x2 *)(p0 + dx * 8);
+                                const int slot = (vy + 1 + tap_dy[k][j2]) & (kPairRing - 1); // slot_of(vy - 1 + dy)
+                                two[j2] = *(const u32x2 *)((const uint8_t *)&s_pix[0][0][0] + slot * (kHaloW * 8) + tap_col8[k][j2]);
                             }
                             const u32x4 both = {two[0][0], two[0][1], two[1][0], two[1][1]};
                             bfrag[k] = __builtin_bit_cast(bf16x8, both);
@@ -1091,6 +1106,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
                 // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
                 const float *si = &s_initA[cb * 32 + hf * 16];
+                const uint32_t dbase = dither16(x, 2 * pa.s);
                 // WIDE: the last two columns of the block also go to the seam: the workgroup's own (for its next
                 // column block) or the image's (the tile's last two columns, for conv_seam_kernel)
                 uint8_t *seam_rows = nullptr;
@@ -1108,7 +1124,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll
                     for (int r = 0; r < RW; ++r) {
                         const int y = 2 * pa.s + r;
-                        const uint32_t dth = dither16(x, y);
+                        const uint32_t dth = dbase ^ ((uint32_t)r << 15);
                         u32x4 pk;
                         pk[0] = pack_bf16_relu(acc[r][8 * hq + 0] + b0[0], acc[r][8 * hq + 1] + b0[1], dth, true);
                         pk[1] = pack_bf16_relu(acc[r][8 * hq + 2] + b0[2], acc[r][8 * hq + 3] + b0[3], dth, true);
