@@ -1043,17 +1043,36 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             tap_dy[k][j2] = tap / 3;
             tap_col8[k][j2] = (xb * 32 + px + tap % 3) * 8;
         }
+    // WIDE, group A: the last two columns (62, 63) of the intermediate rows written in this step, read back from
+    // the ring (the wavefront's own writes) and stored to the seam rows at `rows` (null: nothing to hand over).
+    // Issued behind the step's wait for global memory, so that the wait never has to sit out these stores.
+    auto seam_flush = [&](uint8_t *rows, int sg) {
+        if (!rows || xb != 1) return;
+        const int ln = pin_in_loop(tid & 63);
+        const int pxl = ln & 31, hf = ln >> 5;
+        if (pxl >= 30) {
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int hq = 0; hq < 2; ++hq) {
+                    const u32x4 v = *(const u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + kSkew + 32 + pxl) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2);
+                    *(u32x4 *)(rows + r * kSeamRowBytes + (pxl - 30) * (C * 2) + (cb * 32 + hf * 16 + 8 * hq) * 2) = v;
+                }
+        }
+    };
     f32x16 acc[RW];
     const int n_steps = n_cnt * J * P + 2;
     const size_t seam_half = (size_t)(2 * S) * kSeamRowBytes; // one of a workgroup's two seam buffers
 #pragma unroll 1
     for (int sg = 0; sg < n_steps; ++sg) {
         const bool fin = pf.i >= 0 && pf.i < n_cnt && pf.s < S; // rows accumulated in the previous step wait for their epilogue
+        uint8_t *seam_rows_step = nullptr;
         if (grp == 0) {
             const int ln = pin_in_loop(tid & 63);
             const int pxl = ln & 31, hf = ln >> 5;
             const int xl = xb * 32 + pxl;          // this lane's column within the block
             const int x = pa.b * kTileW + xl;      // and within the tile
+            uint8_t *seam_rows = nullptr;          // WIDE: where the seam columns of this step's rows go, if anywhere
             // FIRST: the raw pixels of virtual rows 2sg+3, 2sg+4 (window of step sg+1) start their way into registers
             uint32_t pv[2] = {0, 0}, psh[2] = {0, 0};
             bool pin[2] = {false, false};
@@ -1107,16 +1126,12 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
                 const float *si = &s_initA[cb * 32 + hf * 16];
                 const uint32_t dbase = dither16(x, 2 * pa.s);
-                // WIDE: the last two columns of the block also go to the seam: the workgroup's own (for its next
-                // column block) or the image's (the tile's last two columns, for conv_seam_kernel)
-                uint8_t *seam_rows = nullptr;
+                // WIDE: the last two columns of the block also go to the seam (seam_flush below): the workgroup's
+                // own (for its next column block) or the image's (the tile's last two columns, for conv_seam_kernel)
                 if (WIDE) {
-                    // (FIRST: the stores of the previous step - this group's only ones - are done before this
-                    // step's follow; a seam row is read a whole unit, at least two steps, after it was written)
-                    if (FIRST) __builtin_amdgcn_s_waitcnt(kWaitVm0);
                     if (pa.b + 1 < J) seam_rows = st.seam + ((size_t)blockIdx.x * 2 + (pa.b & 1)) * seam_half;
                     else if (st.seam_last) seam_rows = st.seam_last + (size_t)(n_begin + pa.i) * seam_half;
-                    if (seam_rows) seam_rows += (size_t)(2 * pa.s) * kSeamRowBytes + (cb * 32 + hf * 16) * 2;
+                    if (seam_rows) seam_rows += (size_t)(2 * pa.s) * kSeamRowBytes;
                 }
 #pragma unroll
                 for (int hq = 0; hq < 2; ++hq) {
@@ -1132,8 +1147,6 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                         pk[3] = pack_bf16_relu(acc[r][8 * hq + 6] + b1[2], acc[r][8 * hq + 7] + b1[3], dth, true);
                         if (y >= g.h || x >= g.w) pk = (u32x4){0u, 0u, 0u, 0u};
                         *(u32x4 *)(ring_mid + slot_of(2 * sg + r) * ROWB + (1 + kSkew + xl) * K::PS + (cb * 32 + hf * 16 + 8 * hq) * 2) = pk;
-                        if (WIDE && seam_rows && xl >= kTileW - 2)
-                            *(u32x4 *)(seam_rows + r * kSeamRowBytes + (xl - (kTileW - 2)) * (C * 2) + 8 * hq * 2) = pk;
                     }
                 }
             } else if (pa.i < n_cnt) { // the rows below the tile: zero padding of the second block (and above the next image)
@@ -1145,10 +1158,16 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                             (u32x4){0u, 0u, 0u, 0u};
                 if (!FIRST && pa.b == J - 1 && pa.i + 1 < n_cnt) prepare_init(n_begin + pa.i + 1); // nobody reads s_initA in this step
             }
+            // WIDE: once per step this group waits for all of its global memory traffic, at a point where it has
+            // to wait for its loads anyway; the stores of the previous step are then known to be done, among them
+            // the seam rows, which are read back a whole unit - at least two steps - after they were written.
+            if (FIRST && WIDE) __builtin_amdgcn_s_waitcnt(kWaitVm0);
             if (FIRST && fetch) { // their slots were last read two steps ago; before the stores below, which need not be waited for
 #pragma unroll
                 for (int k = 0; k < 2; ++k) pixel_store(2 * sg + 3, tid + 256 * k, pv[k], psh[k], pin[k]);
             }
+            if (FIRST && WIDE) seam_flush(seam_rows, sg);
+            seam_rows_step = seam_rows;
             if (FIRST && fin) { // the rows group B accumulated in the previous step
                 const float *srcx = &s_accx[((((sg - 3) & 1) * 4 + w4) * 8) * 256 + ln * 4];
                 f32x16 a[RW];
@@ -1199,6 +1218,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         // image after it when that step is the one of the padding rows.
         if (!FIRST && grp == 0) { // group A has time to spare at the end of a step, group B is the critical path
             __builtin_amdgcn_s_waitcnt(kWaitVm0);
+            if (WIDE) seam_flush(seam_rows_step, sg);
             if (pl.i < n_cnt) {
                 const bool nxt = pl.s == S;
                 const Pos lu = nxt ? next_unit(pl) : pl;
