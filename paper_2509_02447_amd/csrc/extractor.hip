@@ -1265,6 +1265,21 @@ __global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restric
         for (int i = threadIdx.x; i < stat_rec(C, 9); i += 128) s_rec[i] = 0.f;
         __syncthreads();
     }
+    // all operands are asked for before the first is used (unconditional loads from a clamped row; what lies
+    // outside the tile is dropped afterwards): the launch is bound by memory latency, not by its 24 matrix instructions
+    u32x4 bv[3][2][K::KC];
+    bf16x8 av[3][2][K::KC];
+#pragma unroll
+    for (int dy = 0; dy < 3; ++dy) {
+        const int yc = clampi(r + dy - 1, 0, g.h - 1);
+#pragma unroll
+        for (int dx = 0; dx < 2; ++dx)
+#pragma unroll
+            for (int kc = 0; kc < K::KC; ++kc) {
+                bv[dy][dx][kc] = *(const u32x4 *)(sl + (size_t)yc * kSeamRowBytes + dx * (C * 2) + (kc * 16 + half * 8) * 2);
+                av[dy][dx][kc] = wp[((dy * 3 + dx) * K::KC + kc) * 64];
+            }
+    }
     f32x16 sum = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dy = 0; dy < 3; ++dy) {
@@ -1274,9 +1289,8 @@ __global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restric
         for (int dx = 0; dx < 2; ++dx)
 #pragma unroll
             for (int kc = 0; kc < K::KC; ++kc) {
-                u32x4 b = {0u, 0u, 0u, 0u};
-                if (ok) b = *(const u32x4 *)(sl + (size_t)y * kSeamRowBytes + dx * (C * 2) + (kc * 16 + half * 8) * 2);
-                sum = mfma32(wp[((dy * 3 + dx) * K::KC + kc) * 64], __builtin_bit_cast(bf16x8, b), sum);
+                const u32x4 b = ok ? bv[dy][dx][kc] : (u32x4){0u, 0u, 0u, 0u};
+                sum = mfma32(av[dy][dx][kc], __builtin_bit_cast(bf16x8, b), sum);
             }
     }
     const float *bp = biasB + cb * 32 + half * 16;
@@ -1587,10 +1601,11 @@ __global__ __launch_bounds__(256, 4) void conv_first_kernel(TileSrc src, ConvGeo
 //   (dy = 0 never reaches the last row, dy = 2 never the first; same for dx and columns).
 // IPB images per block share every weight read.
 // ------------------------------------------------------------------------------------------------
-constexpr int kHeadIpb = 2;   // images per block
-constexpr int kHeadKParts = 4; // the k = (channel, tap) range is cut in four, one part per 64 threads
+constexpr int kHeadIpb = 1;   // images per block (a launch of a few hundred images should reach every compute unit)
+constexpr int kHeadKParts = 8; // the k = (channel, tap) range is cut in eight, one part per 64 threads
+constexpr int kHeadThreads = 64 * kHeadKParts;
 
-__global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ recs, int slots, int C, int n_img,
+__global__ __launch_bounds__(kHeadThreads) void head_kernel(const float *__restrict__ recs, int slots, int C, int n_img,
                                                    int n_bits, int nbp, float inv_hw,
                                                    const float *__restrict__ wft /*[C*9][nbp]*/,
                                                    const float *__restrict__ fbias, const float *__restrict__ lin_w,
@@ -1605,7 +1620,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ rec
     const int tid = threadIdx.x;
     const int64_t n0 = (int64_t)blockIdx.x * kHeadIpb;
     const int rec = stat_rec(C, 9);
-    for (int idx = tid; idx < kHeadIpb * 9 * C; idx += 256) {
+    for (int idx = tid; idx < kHeadIpb * 9 * C; idx += kHeadThreads) {
         const int i = idx / (9 * C), r = idx - i * 9 * C; // r = q*C + c
         float v = 0.f;
         if (n0 + i < n_img)
@@ -1613,7 +1628,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ rec
         Q[i][r / C][r % C] = v;
     }
     __syncthreads();
-    for (int idx = tid; idx < kHeadIpb * C; idx += 256) {
+    for (int idx = tid; idx < kHeadIpb * C; idx += kHeadThreads) {
         const int i = idx / C, c = idx - i * C;
         const float T = Q[i][0][c], R0 = Q[i][1][c], Rl = Q[i][2][c], C0 = Q[i][3][c], Cl = Q[i][4][c];
         const float c00 = Q[i][5][c], c0l = Q[i][6][c], cl0 = Q[i][7][c], cll = Q[i][8][c];
@@ -1651,7 +1666,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ rec
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < kHeadIpb * n_bits; idx += 256) {
+    for (int idx = tid; idx < kHeadIpb * n_bits; idx += kHeadThreads) {
         const int i = idx / n_bits, o = idx - i * n_bits;
         float v = 0.f;
 #pragma unroll
@@ -1659,7 +1674,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ rec
         pooled[i][o] = v * inv_hw + (fbias ? fbias[o] : 0.f);
     }
     __syncthreads();
-    for (int idx = tid; idx < kHeadIpb * n_bits; idx += 256) {
+    for (int idx = tid; idx < kHeadIpb * n_bits; idx += kHeadThreads) {
         const int i = idx / n_bits, o = idx - i * n_bits;
         float z = lin_b ? lin_b[o] : 0.f;
         for (int k = 0; k < n_bits; ++k) z = fmaf(lin_w[o * n_bits + k], pooled[i][k], z);
@@ -1673,7 +1688,7 @@ __global__ __launch_bounds__(256) void head_kernel(const float *__restrict__ rec
     __syncthreads();
     if (symbols) {
         const int nsym = n_bits / m;
-        for (int idx = tid; idx < kHeadIpb * nsym; idx += 256) {
+        for (int idx = tid; idx < kHeadIpb * nsym; idx += kHeadThreads) {
             const int i = idx / nsym, j = idx - i * nsym;
             if (n0 + i < n_img) {
                 int sym = 0;
@@ -1832,7 +1847,7 @@ hipError_t launch_head(const float *recs, int slots, int C, int64_t n_img, int n
 {
     if (n_img <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((n_img + kHeadIpb - 1) / kHeadIpb);
-    hipLaunchKernelGGL(head_kernel, dim3(blocks), dim3(256), 0, s, recs, slots, C, (int)n_img, n_bits, nbp, inv_hw, wft,
+    hipLaunchKernelGGL(head_kernel, dim3(blocks), dim3(kHeadThreads), 0, s, recs, slots, C, (int)n_img, n_bits, nbp, inv_hw, wft,
                        fbias, lin_w, lin_b, logits, bits, symbols, m);
     return hipGetLastError();
 }
