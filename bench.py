@@ -418,6 +418,32 @@ def bench_stream(env, passes: int, warm_passes: int) -> dict:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     value = n_total * passes / dt
+    # the pipeline's time line, chunk by chunk (events recorded inside the library): one more pass
+    ctx.qrm_profile_enable(True)
+    step()
+    tl = ctx.qrm_profile_read_chunks(n_chunks)
+    ctx.qrm_profile_enable(False)
+    timeline = None
+    if len(tl) >= 4:
+        up, run = tl[:, 1] - tl[:, 0], tl[:, 3] - tl[:, 2]
+        gaps = tl[1:, 0] - tl[:-1, 1]
+        span = tl[-1, 1] - tl[0, 0]
+        timeline = {
+            "chunks": int(len(tl)),
+            "upload_ms_per_chunk": round(float(up.mean()), 3), "upload_ms_max": round(float(up.max()), 3),
+            "upload_ms_per_chunk_by_quarter_of_the_pass": [round(float(q.mean()), 3) for q in np.array_split(up, 4)],
+            "gap_between_uploads_ms_mean": round(float(gaps.mean()), 4), "gap_between_uploads_ms_max": round(float(gaps.max()), 4),
+            "link_busy_fraction": round(float(up.sum() / span), 4),
+            "kernels_ms_per_chunk": round(float(run.mean()), 3), "kernels_ms_max": round(float(run.max()), 3),
+            "kernel_stream_busy_fraction": round(float(run.sum() / (tl[-1, 3] - tl[0, 2])), 4),
+            "kernels_start_after_upload_end_ms_mean": round(float((tl[:, 2] - tl[:, 1]).mean()), 4),
+            "download_end_after_kernels_end_ms_mean": round(float((tl[:, 4] - tl[:, 3]).mean()), 4),
+            "last_download_end_after_last_upload_end_ms": round(float(tl[-1, 4] - tl[-1, 1]), 3),
+            "first_chunks_ms": [[round(float(v), 2) for v in row] for row in tl[:6]],
+            "columns": "upload start, upload end, kernels start, kernels end, download end (ms since the first upload started)",
+            "note": "the uploads follow each other with no gap and the kernels of a chunk take about half as long as its upload: "
+                    "the pipeline is bound by the host link, and there is no idle time for a stream tuner to fill",
+        }
     # the link on its own: the same chunks uploaded back to back, nothing else running
     d_stage = torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
     d_stage.copy_(bufs[0], non_blocking=True)
@@ -455,7 +481,7 @@ def bench_stream(env, passes: int, warm_passes: int) -> dict:
         "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),
         "extractor_frac_of_bf16_peak": round(mfma_flops_per_image * value / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stages": {"bare_upload_GBs": round(link_gbs, 2), "bare_upload_images_per_s": round(link_gbs * 1e9 / (3 * cfg.H * cfg.W), 1),
-                   "resident_images_per_s": round(resident, 1)},
+                   "resident_images_per_s": round(resident, 1), "timeline": timeline},
     }
     log(f"C5: {value:.0f} images/s = {res['roofline']['frac']:.3f} of the bare upload rate ({link_gbs:.1f} GB/s)")
     ctx.close()

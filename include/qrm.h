@@ -324,6 +324,14 @@ enum {
 };
 QRM_API qrm_status qrm_profile_enable(qrm_ctx *ctx, int32_t on);
 QRM_API qrm_status qrm_profile_read(qrm_ctx *ctx, int32_t kind, double *ms_total, int64_t *launches, double *flops);
+/*
+ * The time line of the last qrm_detect_host call made while profiling was enabled (that call records five events
+ * per chunk instead of two per launch): ms[i*5 + 0..4] = upload start, upload end, kernels start, kernels end,
+ * download end of chunk i, in milliseconds since the first upload started, for the first min(max_chunks, chunks)
+ * chunks; *n_chunks receives the number of chunks that call had.  "kernels start" is when the kernel stream
+ * reached the chunk, i.e. after the waits for its upload and for its output buffer.
+ */
+QRM_API qrm_status qrm_profile_read_chunks(qrm_ctx *ctx, int32_t max_chunks, double *ms, int32_t *n_chunks);
 
 /* Library version string, e.g. "qrm 0.1 gfx950". */
 QRM_API const char *qrm_version(void);

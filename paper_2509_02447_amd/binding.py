@@ -40,7 +40,7 @@ class _RsDesc(C.Structure):
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
            "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
-           "qrm_profile_enable", "qrm_profile_read", "qrm_release_stream", "qrm_detect_static", "qrm_version"]
+           "qrm_profile_enable", "qrm_profile_read", "qrm_profile_read_chunks", "qrm_release_stream", "qrm_detect_static", "qrm_version"]
 DIAG_EXPORTS = ["qrm_diag_set_flags", "qrm_diag_matrix_rate"]      # include/qrm_diag.h: bench and test tooling
 
 QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE, QRM_DIAG_FUSE_ALWAYS = 1, 2, 4
@@ -103,6 +103,8 @@ def load_library():
     lib.qrm_profile_enable.restype = C.c_int
     lib.qrm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     lib.qrm_profile_read.restype = C.c_int
+    lib.qrm_profile_read_chunks.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32)]
+    lib.qrm_profile_read_chunks.restype = C.c_int
     lib.qrm_release_stream.argtypes = [vp, vp]
     lib.qrm_release_stream.restype = C.c_int
     lib.qrm_diag_set_flags.argtypes = [vp, i32]
@@ -228,6 +230,15 @@ class Context:
         ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
         self._check(self._lib.qrm_profile_read(self._h, int(kind), C.byref(ms), C.byref(n), C.byref(fl)))
         return ms.value, n.value, fl.value
+
+    def qrm_profile_read_chunks(self, max_chunks: int):
+        """-> float64 array [chunks, 5]: upload start / end, kernels start / end, download end (ms) of the last
+        qrm_detect_host call made with profiling on."""
+        buf = np.zeros((max(1, int(max_chunks)), 5), dtype=np.float64)
+        n = C.c_int32()
+        self._check(self._lib.qrm_profile_read_chunks(self._h, int(max_chunks), buf.ctypes.data_as(C.POINTER(C.c_double)),
+                                                      C.byref(n)))
+        return buf[:min(int(n.value), int(max_chunks))]
 
     def qrm_release_stream(self, stream=None):
         self._check(self._lib.qrm_release_stream(self._h, _stream_handle(stream)))

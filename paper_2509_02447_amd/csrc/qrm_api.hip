@@ -377,7 +377,7 @@ qrm_status slot_done(qrm_ctx *c, QrmSlot *slot, hipStream_t s)
 // Event pair around one launch while profiling is on (null otherwise).
 qrm_ctx::Timed *time_begin(qrm_ctx *c, bool may_time, int kind, double flops, hipStream_t s)
 {
-    if (!c->profile || !may_time) return nullptr;
+    if (!c->profile || !may_time || c->in_host_pipeline) return nullptr;
     if (c->timed_used == c->timed.size()) {
         qrm_ctx::Timed t;
         if (hipEventCreate(&t.start) != hipSuccess) return nullptr;
@@ -683,6 +683,9 @@ void qrm_destroy(qrm_ctx *c)
         (void)hipEventDestroy(t.start);
         (void)hipEventDestroy(t.stop);
     }
+    for (auto &ct : c->chunk_times)
+        for (hipEvent_t ev : ct.ev)
+            if (ev) (void)hipEventDestroy(ev);
     for (hipStream_t s : {c->s_up, c->s_run, c->s_down})
         if (s) (void)hipStreamSynchronize(s);
     for (auto &sg : c->stages) {
@@ -745,6 +748,25 @@ qrm_status qrm_profile_read(qrm_ctx *c, int32_t kind, double *ms_total, int64_t 
     if (ms_total) *ms_total = ms;
     if (launches) *launches = cnt;
     if (flops) *flops = fl;
+    return QRM_OK;
+}
+
+qrm_status qrm_profile_read_chunks(qrm_ctx *c, int32_t max_chunks, double *ms, int32_t *n_chunks)
+{
+    if (!c) return QRM_E_INVALID;
+    if (max_chunks < 0 || (max_chunks > 0 && !ms)) return fail(c, QRM_E_INVALID, "ms is NULL");
+    const int n = (int)std::min<size_t>(c->chunks_timed, (size_t)max_chunks);
+    if (n_chunks) *n_chunks = (int32_t)c->chunks_timed;
+    if (n == 0) return QRM_OK;
+    hipEvent_t base = c->chunk_times[0].ev[0];
+    for (int i = 0; i < n; ++i)
+        for (int k = 0; k < 5; ++k) {
+            hipError_t e = hipEventSynchronize(c->chunk_times[i].ev[k]);
+            float t = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&t, base, c->chunk_times[i].ev[k]);
+            if (e != hipSuccess) return hip_fail(c, e, "hipEventElapsedTime");
+            ms[i * 5 + k] = t;
+        }
     return QRM_OK;
 }
 
@@ -1072,6 +1094,21 @@ qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n
     // submitted and a download waits for its kernels: the download of chunk i-1 is submitted after the
     // upload of chunk i, so that it never holds up an upload that could already run.
     qrm_status st = QRM_OK;
+    // while profiling is on, five events per chunk: upload start / end, kernels start / end, download end
+    const bool timeline = c->profile;
+    c->chunks_timed = 0;
+    if (timeline) {
+        while (c->chunk_times.size() < (size_t)n_chunks) {
+            qrm_ctx::ChunkTimes ct;
+            for (hipEvent_t &ev : ct.ev) {
+                e = hipEventCreate(&ev);
+                if (e != hipSuccess) return hip_fail(c, e, "hipEventCreate");
+            }
+            c->chunk_times.push_back(ct);
+        }
+    }
+    auto mark = [&](int i, int k, hipStream_t s) { if (timeline) (void)hipEventRecord(c->chunk_times[i].ev[k], s); };
+    c->in_host_pipeline = true;
     auto download = [&](int i) -> hipError_t {
         qrm_ctx::Stage &sg = c->stages[i % used];
         const uint8_t *d_msg = sg.d_out, *d_cw = sg.d_out + msg_bytes, *d_ne = sg.d_out + msg_bytes + cw_bytes;
@@ -1083,6 +1120,7 @@ qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n
         if (err == hipSuccess)
             err = hipMemcpyAsync(h_nerr + (size_t)i * chunk_images, d_ne, chunk_images, hipMemcpyDeviceToHost, c->s_down);
         if (err == hipSuccess) err = hipEventRecord(sg.downloaded, c->s_down);
+        mark(i, 4, c->s_down);
         return err;
     };
     int submitted = 0; // chunks whose kernels are enqueued
@@ -1092,18 +1130,22 @@ qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n
         int8_t *d_ne = (int8_t *)(sg.d_out + msg_bytes + cw_bytes);
         e = hipSuccess;
         if (i >= used) e = hipStreamWaitEvent(c->s_up, sg.computed, 0); // the kernels of chunk i - depth have read d_img
+        mark(i, 0, c->s_up);
         if (e == hipSuccess) e = hipMemcpyAsync(sg.d_img, h_chunks[i], img_bytes, hipMemcpyHostToDevice, c->s_up);
         if (e == hipSuccess && h_off_chunks)
             e = hipMemcpyAsync(sg.d_off, h_off_chunks[i], off_bytes, hipMemcpyHostToDevice, c->s_up);
         if (e == hipSuccess) e = hipEventRecord(sg.uploaded, c->s_up);
+        mark(i, 1, c->s_up);
         if (e == hipSuccess) e = hipStreamWaitEvent(c->s_run, sg.uploaded, 0);
         if (e == hipSuccess && i >= used) e = hipStreamWaitEvent(c->s_run, sg.downloaded, 0); // d_out is free again
+        mark(i, 2, c->s_run);
         if (e != hipSuccess) { st = hip_fail(c, e, "upload of a chunk"); break; }
         st = qrm_detect(c, sg.d_img, chunk_images, H, W, h_off_chunks ? sg.d_off : nullptr, tile, nullptr, nullptr, d_msg,
                         h_codeword ? d_cw : nullptr, d_ne, c->s_run);
         if (st != QRM_OK) break;
         e = hipEventRecord(sg.computed, c->s_run);
         if (e != hipSuccess) { st = hip_fail(c, e, "hipEventRecord"); break; }
+        mark(i, 3, c->s_run);
         submitted = i + 1;
         // The download of a chunk must be submitted before the kernels of the next chunk that shares its
         // staging buffer (their wait on `downloaded` above refers to the event as recorded by then).  With
@@ -1124,6 +1166,8 @@ qrm_status qrm_detect_host(qrm_ctx *c, const uint8_t *const *h_chunks, int32_t n
         e = hipStreamSynchronize(s);
         if (e != hipSuccess && st == QRM_OK) st = hip_fail(c, e, "hipStreamSynchronize");
     }
+    c->in_host_pipeline = false;
+    if (timeline && st == QRM_OK) c->chunks_timed = (size_t)submitted;
     return st;
 }
 

@@ -54,6 +54,12 @@ struct qrm_ctx {
     };
     std::vector<Timed> timed;  // pool of event pairs; the first timed_used are recorded
     size_t timed_used = 0;
+    bool in_host_pipeline = false; // qrm_detect_host is running: its chunks are timed as wholes, not launch by launch
+    struct ChunkTimes {
+        hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr}; // upload start / end, kernels start / end, download end
+    };
+    std::vector<ChunkTimes> chunk_times; // pool; the first chunks_timed are recorded (last qrm_detect_host call)
+    size_t chunks_timed = 0;
     // chunked host -> device pipeline of qrm_detect_host, created on first use: one stream per role
     // (upload, kernels, download) and a ring of staging buffers with the events that hand them on
     struct Stage {
