@@ -91,9 +91,6 @@ typedef short s16x2 __attribute__((ext_vector_type(2)));
 // fractions of vertically neighbouring pixels evenly.
 __device__ __forceinline__ uint32_t dither16(int x, int y)
 {
-#ifdef QRM_EXP_NODITHER
-    return 0x8000u;
-#endif
     uint32_t h = (uint32_t)x * 0x9E3779B1u + (uint32_t)y * 0x85EBCA77u;
     h ^= h >> 15;
     h = __umul24(h, 0x00C1B3C5u); // low 24 bits x 24 bits: the product's upper half depends on all of them
@@ -305,6 +302,42 @@ __device__ __forceinline__ float half_sum(float v)
     v += dpp_f<0x140, 0xf>(v); // row_mirror
     v += dpp_f<0x142, 0xa>(v); // row_bcast:15 into rows 1 and 3
     return v;
+}
+
+// Sums of 16 values per lane over the 32 pixel lanes of one half-wavefront, handed out one value per lane: a
+// butterfly that halves the number of values a lane holds while it doubles the number of lanes summed (rows of
+// 16 lanes are paired with v_permlane16_swap, then lanes p and 15-p, p and 7-p within 8, p and p^2, p and p^1 with
+// DPP moves), 38 instructions instead of 80 for sixteen separate 32-lane sums.  Lane (pxl) ends up with the sum of
+// value number reduce16_index(pxl); lanes p and p^1 hold the same one.
+__device__ __forceinline__ int reduce16_index(int pxl) { return ((pxl >> 4) & 1) * 8 + ((pxl >> 3) & 1) * 4 + ((pxl >> 2) & 1) * 2 + ((pxl >> 1) & 1); }
+__device__ __forceinline__ float reduce16_over_half(const float (&t)[16], int pxl)
+{
+    float u[8], w[4], x2[2], lo[8], hi[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { lo[j] = t[j]; hi[j] = t[j + 8]; }
+    // v_permlane16_swap_b32 a, b: rows 1 and 3 of a <-> rows 0 and 2 of b.  As assembly: this compiler's builtin
+    // hands back the first register for both results.  The instruction must not read a register a vector
+    // instruction wrote in the two cycles before it, hence the s_nop in front (the compiler, which keeps such
+    // distances for its own instructions, does not look into assembly); the operands are sums the compiler's own
+    // instructions formed, so the longer distance behind a matrix instruction has been kept by then.
+    asm volatile("s_nop 1\n\t"
+                 "v_permlane16_swap_b32 %0, %8\n\tv_permlane16_swap_b32 %1, %9\n\t"
+                 "v_permlane16_swap_b32 %2, %10\n\tv_permlane16_swap_b32 %3, %11\n\t"
+                 "v_permlane16_swap_b32 %4, %12\n\tv_permlane16_swap_b32 %5, %13\n\t"
+                 "v_permlane16_swap_b32 %6, %14\n\tv_permlane16_swap_b32 %7, %15\n\t"
+                 "s_nop 1"
+                 : "+v"(lo[0]), "+v"(lo[1]), "+v"(lo[2]), "+v"(lo[3]), "+v"(lo[4]), "+v"(lo[5]), "+v"(lo[6]), "+v"(lo[7]),
+                   "+v"(hi[0]), "+v"(hi[1]), "+v"(hi[2]), "+v"(hi[3]), "+v"(hi[4]), "+v"(hi[5]), "+v"(hi[6]), "+v"(hi[7]));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u[j] = lo[j] + hi[j]; // rows 0, 2: value j over both rows; rows 1, 3: value j + 8
+    const bool b3 = (pxl & 8) != 0, b2 = (pxl & 4) != 0, b1 = (pxl & 2) != 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = (b3 ? u[j + 4] : u[j]) + dpp_f<0x140, 0xf>(b3 ? u[j] : u[j + 4]);      // row_mirror
+#pragma unroll
+    for (int j = 0; j < 2; ++j) x2[j] = (b2 ? w[j + 2] : w[j]) + dpp_f<0x141, 0xf>(b2 ? w[j] : w[j + 2]);    // row_half_mirror
+    float y = (b1 ? x2[1] : x2[0]) + dpp_f<0x4E, 0xf>(b1 ? x2[0] : x2[1]);                                    // quad_perm [2,3,0,1]
+    y += dpp_f<0xB1, 0xf>(y);                                                                                   // quad_perm [1,0,3,2]
+    return y;
 }
 
 // lanes with `pred` add their 16 values into this wavefront's private LDS accumulators
@@ -909,7 +942,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         return Pos{i, u - i * J, sigma - u * P};
     };
     auto advance = [P, J](Pos &p) {
-        if (++p.s == P) {
+        if (__builtin_expect(++p.s == P, 0)) { // once per unit: kept out of the way of the other steps
             p.s = 0;
             if (++p.b == J) {
                 p.b = 0;
@@ -957,6 +990,68 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
         for (int i = tid - 256; i < SLOTS; i += 256) *(u32x4 *)(ring_mid + slot_of(-1) * ROWB + i * 16) = (u32x4){0u, 0u, 0u, 0u};
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();
+
+    // LASTB: the nine border-aware channel sums of the last block's output (see strip_statistics) from the two
+    // rows in `a`.  The sum over the whole tile, the only one every pixel goes into, is kept in a register per
+    // lane: the 16 channel values of a lane (both rows added) go through one butterfly over the 32 pixel lanes,
+    // after which every lane holds the sum of one channel and adds it to its running total (run_sum; written to
+    // the record when the image is done).  First / last column: the one lane that holds it adds its 16 values
+    // to the LDS accumulators, in the wavefronts that contain such a column only.  First / last row and the four
+    // corners: the same for that row alone, in the (two) steps that contain those rows.
+    float run_sum = 0.f;
+    auto last_block_statistics = [&](const f32x16 (&a)[RW], const float *si, int x, int x0w, int j, int pxl, int hf) {
+        float *stat = &s_stat[w4][0][hf * 16]; // + sum index * 32 + channel
+        const bool colok = (uint32_t)x < (uint32_t)g.w;
+        const bool allcols = x0w >= 0 && x0w + 32 <= g.w; // same for the whole wavefront
+        const bool row1 = 2 * j + 1 < g.h;                // (row 2j always lies in the tile)
+        const bool has_first = x0w <= 0 && x0w + 32 > 0, has_last = x0w <= g.w - 1 && g.w - 1 < x0w + 32;
+        float bias[16], t[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f32x4 bq = *(const f32x4 *)(si + 4 * q);
+            bias[4 * q] = bq[0]; bias[4 * q + 1] = bq[1]; bias[4 * q + 2] = bq[2]; bias[4 * q + 3] = bq[3];
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float r1 = fmaxf(a[1][v] + bias[v], 0.f);
+            t[v] = fmaxf(a[0][v] + bias[v], 0.f) + (row1 ? r1 : 0.f);
+        }
+        if (!allcols) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) t[v] = colok ? t[v] : 0.f;
+        }
+        auto column = [&](float *dst, const float (&val)[16], bool pred) { // one lane's 16 values into 16 accumulators
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float four[4] = {val[4 * q], val[4 * q + 1], val[4 * q + 2], val[4 * q + 3]};
+                lds_accumulate4(dst + 4 * q, four, pred);
+            }
+        };
+        if (has_first) column(stat + 3 * 32, t, x == 0);
+        if (has_last) column(stat + 4 * 32, t, x == g.w - 1);
+        run_sum += reduce16_over_half(t, pxl);
+        const int rl = g.h - 1 - 2 * j; // the tile's last row, counted from this pair's first
+        if (j == 0 || rl < RW) { // the tile's first and / or last row is one of the two
+#pragma unroll 1
+            for (int which = 0; which < 2; ++which) {
+                if (which == 0 ? j != 0 : (rl < 0 || rl >= RW)) continue;
+                const bool second = which == 1 && rl == 1;
+                float rv[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float av = second ? a[1][v] : a[0][v];
+                    rv[v] = colok ? fmaxf(av + bias[v], 0.f) : 0.f;
+                }
+                const float y = reduce16_over_half(rv, pxl);
+                if ((pxl & 1) == 0) { // (an LDS add, as in lds_accumulate4)
+                    const lrow_t ad = lds_address(stat + (1 + which) * 32 + reduce16_index(pxl));
+                    asm volatile("ds_add_f32 %0, %1" : : "v"(ad), "v"(y) : "memory");
+                }
+                if (has_first) column(stat + (5 + 2 * which) * 32, rv, x == 0);
+                if (has_last) column(stat + (6 + 2 * which) * 32, rv, x == g.w - 1);
+            }
+        }
+    };
 
     // bias, ReLU, bf16, stores (or nothing: LASTB) and statistics of output rows 2j, 2j+1 of column block blk of
     // image n held in `a`; after the last row pair of an image its channel sums go to its records and the
@@ -1006,8 +1101,12 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
             }
         }
-        if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) { // (the rows conv_mid would sample)
-            strip_statistics<RW, LASTB>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
+        if (LASTB) {
+            if (st.tout) last_block_statistics(a, si, x, x_lo + xb * 32, j, pxl, hf);
+        } else if (st.tout && ((j >> 1) & 7) == sample_phase) { // (the rows conv_mid would sample)
+            strip_statistics<RW, false>(a, si, &s_stat[w4][0][hf * 16], x, 2 * j, g.h, g.w, pxl);
+        }
+        if (st.tout && (LASTB || ((j >> 1) & 7) == sample_phase)) {
             if (cb == 0 && ln == 0) {
                 const int rows = max(0, min(RW, g.h - 2 * j));
                 const int cols = max(0, min(x_lo + xb * 32 + 32, g.w) - max(x_lo + xb * 32, 0));
@@ -1015,6 +1114,10 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             }
         }
         if (st.tout && j == S - 1 && blk == J - 1) { // what this wavefront gathered for the image (its own part of s_stat)
+            if (LASTB) { // the whole-tile sums lived in a register: one channel per lane
+                if ((pxl & 1) == 0) s_stat[w4][0][hf * 16 + reduce16_index(pxl)] = run_sum;
+                run_sum = 0.f;
+            }
             float *rec = st.tout + ((int64_t)n * st.out_slots + xb) * stat_rec(C, NQ);
             if (ln < 32) {
 #pragma unroll
@@ -1060,9 +1163,46 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
         }
     };
+    // !FIRST, group A, in the middle of its step (between its matrix work and its epilogue): what the wavefront
+    // issued a step ago - the two input rows of the step after this one, the seam columns - is waited for, then the
+    // two rows needed two steps from now are put on their way: rows 2s+1, 2s+2 of the unit of step sg + 2, or rows
+    // -1, 0 of the unit after it when that step is the one of the padding rows.  Their ring slots were last read in
+    // the step before this one.  In the middle of the step, not at its end: the vector-memory instructions of a
+    // compute unit queue up behind each other, and group B's stores at the start of the next step - the critical
+    // path - would otherwise wait behind these twenty loads.
+    auto input_loads = [&](int sg) {
+        __builtin_amdgcn_s_waitcnt(kWaitVm0);
+        if (pl.i < n_cnt) {
+            const bool nxt = pl.s == S;
+            const Pos lu = nxt ? next_unit(pl) : pl;
+            if (lu.i < n_cnt) {
+                issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1), 2 * sg + 5);
+                issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1) + 1, 2 * sg + 6);
+            }
+        }
+    };
+    // WIDE: ring pixels 0 and 1 of the intermediate rows group A writes in this step: the two columns left of its
+    // block, from the seam of the block before (zeros in block 0 and in the padding rows); 2 x 9 slots per row,
+    // straight into LDS.  One wavefront issues them at the start of the step - a wavefront of the group that is
+    // not the step's critical path: vector-memory instructions of a compute unit queue up behind each other, and
+    // right after the barrier the queue still holds what was issued at the end of the previous step - and waits
+    // for them before the step's barrier.
+    const size_t seam_half = (size_t)(2 * S) * kSeamRowBytes; // one of a workgroup's two seam buffers
+    auto seam_loads = [&](int sg) {
+        if (w4 != 0 || pa.i >= n_cnt) return;
+        const int ln = pin_in_loop(tid & 63);
+        const bool have = pa.b > 0 && pa.s < S;
+        const uint8_t *sp = st.seam + ((size_t)blockIdx.x * 2 + ((pa.b & 1) ^ 1)) * seam_half + (size_t)(2 * pa.s) * kSeamRowBytes;
+        const int spx = ln / K::SPP, sslot = ln - spx * K::SPP;
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const uint8_t *p = (have && sslot < C / 8) ? sp + r * kSeamRowBytes + spx * (C * 2) + sslot * 16 : zeros;
+            if (ln < 2 * K::SPP)
+                __builtin_amdgcn_global_load_lds((gptr_t)p, (lptr_t)(ring_mid + slot_of(2 * sg + r) * ROWB), 16, 0, 0);
+        }
+    };
     f32x16 acc[RW];
     const int n_steps = n_cnt * J * P + 2;
-    const size_t seam_half = (size_t)(2 * S) * kSeamRowBytes; // one of a workgroup's two seam buffers
 #pragma unroll 1
     for (int sg = 0; sg < n_steps; ++sg) {
         const bool fin = pf.i >= 0 && pf.i < n_cnt && pf.s < S; // rows accumulated in the previous step wait for their epilogue
@@ -1073,6 +1213,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             const int xl = xb * 32 + pxl;          // this lane's column within the block
             const int x = pa.b * kTileW + xl;      // and within the tile
             uint8_t *seam_rows = nullptr;          // WIDE: where the seam columns of this step's rows go, if anywhere
+            if (WIDE && !FIRST) seam_loads(sg);    // (waited for at the end of the step, with this group's other loads)
             // FIRST: the raw pixels of virtual rows 2sg+3, 2sg+4 (window of step sg+1) start their way into registers
             uint32_t pv[2] = {0, 0}, psh[2] = {0, 0};
             bool pin[2] = {false, false};
@@ -1122,6 +1263,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
 #pragma unroll
                     for (int r = 0; r < RW + 2; ++r) rowp[r] = in_base + (uint32_t)slot_of(2 * sg - 1 + r) * ROWB;
                     strip_mma<C, RW, false, false, true>(rowp, Wr, acc, RW);
+                    input_loads(sg);
                 }
                 // epilogue: + bias and correction, ReLU, bf16 -> intermediate ring (zeros outside the tile)
                 const float *si = &s_initA[cb * 32 + hf * 16];
@@ -1150,6 +1292,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                     }
                 }
             } else if (pa.i < n_cnt) { // the rows below the tile: zero padding of the second block (and above the next image)
+                if (!FIRST) input_loads(sg);
 #pragma unroll
                 for (int r = 0; r < RW; ++r)
 #pragma unroll
@@ -1182,20 +1325,7 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
             }
         } else {
             const int ln = pin_in_loop(tid & 63);
-            if (WIDE && w4 == 0 && pa.i < n_cnt) {
-                // ring pixels 0 and 1 of the intermediate rows group A writes in this step: the two columns left
-                // of its block, from the seam of the block before (zeros in block 0 and in the padding rows);
-                // 2 x 9 slots per row, straight into LDS
-                const bool have = pa.b > 0 && pa.s < S;
-                const uint8_t *sp = st.seam + ((size_t)blockIdx.x * 2 + ((pa.b & 1) ^ 1)) * seam_half + (size_t)(2 * pa.s) * kSeamRowBytes;
-                const int spx = ln / K::SPP, sslot = ln - spx * K::SPP;
-#pragma unroll
-                for (int r = 0; r < RW; ++r) {
-                    const uint8_t *p = (have && sslot < C / 8) ? sp + r * kSeamRowBytes + spx * (C * 2) + sslot * 16 : zeros;
-                    if (ln < 2 * K::SPP)
-                        __builtin_amdgcn_global_load_lds((gptr_t)p, (lptr_t)(ring_mid + slot_of(2 * sg + r) * ROWB), 16, 0, 0);
-                }
-            }
+            if (WIDE && FIRST) seam_loads(sg); // (group A is the critical path of this variant)
             if (!FIRST && fin) finish(acc, n_begin + pf.i, pf.b, pf.s); // the rows accumulated in the previous step
             if (pb.i >= 0 && pb.i < n_cnt && pb.s < S) {
                 lrow_t rowp[RW + 2];
@@ -1212,23 +1342,9 @@ __global__ __launch_bounds__(512, 1) void conv_pair_kernel(const uint8_t *__rest
                 }
             }
         }
-        // End of the step, both groups: what the wavefront issued a step ago (loads; group B's stores
-        // date from the start of this step) is done, then the rows needed two steps from now are put on
-        // their way, one row per group: rows 2s+1, 2s+2 of the image of step sg + 2, or rows -1, 0 of the
-        // image after it when that step is the one of the padding rows.
-        if (!FIRST && grp == 0) { // group A has time to spare at the end of a step, group B is the critical path
-            __builtin_amdgcn_s_waitcnt(kWaitVm0);
-            if (WIDE) seam_flush(seam_rows_step, sg);
-            if (pl.i < n_cnt) {
-                const bool nxt = pl.s == S;
-                const Pos lu = nxt ? next_unit(pl) : pl;
-                if (lu.i < n_cnt) {
-                    issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1), 2 * sg + 5);
-                    issue_row(n_begin + lu.i, lu.b, (nxt ? -1 : 2 * pl.s + 1) + 1, 2 * sg + 6);
-                }
-            }
-        }
-        if (WIDE && grp == 1 && w4 == 0) __builtin_amdgcn_s_waitcnt(kWaitVm0); // the seam columns have landed
+        // End of the step
+        if (!FIRST && WIDE && grp == 0) seam_flush(seam_rows_step, sg);
+        if (WIDE && FIRST && grp == 1 && w4 == 0) __builtin_amdgcn_s_waitcnt(kWaitVm0); // the seam columns have landed
         lds_barrier();
         advance(pa);
         advance(pb);
@@ -1297,7 +1413,7 @@ __global__ __launch_bounds__(128) void conv_seam_kernel(const uint8_t *__restric
     float val[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) val[v] = sum[v] + bp[v];
-    if (!LASTB) {
+    if constexpr (!LASTB) {
         if (r < g.h) {
             bf16_t *dst = out + (((size_t)n * g.h + r) * g.w + (g.w - 1)) * C + cb * 32 + half * 16;
             u32x4 lo, hi;
