@@ -26,6 +26,9 @@
 //    average pool are linear, so nine border-aware channel sums per image are all head_kernel needs to
 //    apply the final convolution (fp32 weights), the linear layer, the threshold and the symbol packing.
 //    With a final ReLU, conv_final_kernel sums the final convolution's output in its accumulators.
+#include <type_traits>
+#include <utility>
+
 #include "qrm_internal.h"
 
 namespace qrm {
@@ -192,6 +195,34 @@ __device__ __forceinline__ void issue_strip_loads(uint8_t *lds, const uint8_t *w
     }
 }
 
+// body(std::integral_constant<int, 0>) ... body(std::integral_constant<int, N - 1>) in this order: a loop whose
+// counter is a compile-time constant inside the body (assembly operands with immediate constraints need one)
+template <int... I, typename F>
+__device__ __forceinline__ void unrolled_impl(std::integer_sequence<int, I...>, F &&body)
+{
+    (body(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void unrolled(F &&body)
+{
+    unrolled_impl(std::make_integer_sequence<int, N>{}, body);
+}
+
+// One matrix operand (16 bytes per lane) from LDS address `row` + OFFSET, and the wait that says it has landed
+// (at most PENDING later LDS operations of the wavefront outstanding).  Assembly, tied to the register: the
+// compiler, not knowing which direct-to-LDS load fills which bytes, would otherwise drain the whole
+// vector-memory queue (stores included) before the first read.
+template <int OFFSET>
+__device__ __forceinline__ void frag_read(bf16x8 &dst, lrow_t row)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(row), "n"(OFFSET));
+}
+template <int PENDING>
+__device__ __forceinline__ void frag_wait(bf16x8 &frag)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(frag) : "n"(PENDING));
+}
+
 // Accumulates RW output rows of one 32-pixel x 32-channel block from the staged strip.
 //
 // The RW + 2 staged rows feed 1, 2, 3, .., 3, 2, 1 vertical taps; rows are paired (p, p + (RW+2)/2) so
@@ -216,47 +247,47 @@ __device__ __forceinline__ void strip_mma(const lrow_t (&rowp)[RW + 2], const bf
     constexpr int NP = (RW + 2) / 2;  // row pairs
     constexpr int KP = K::KC / 2;     // pairs of k chunks
     constexpr int NS = 3 * KP * NP;   // sets
-    bf16x8 f[4];
-    auto set_row = [](int s2, int j) { return (s2 % NP) + (j & 1) * NP; };
-    auto set_kc = [](int s2, int j) { return 2 * ((s2 / NP) % KP) + (j >> 1); };
-    auto set_dx = [](int s2) { return s2 / (NP * KP); };
-#define QRM_FRAG_READ(dst, s2_, j_)                                                                         \
-    asm volatile("ds_read_b128 %0, %1 offset:%2"                                                            \
-                 : "=v"(dst)                                                                                \
-                 : "v"(rowp[set_row(s2_, j_)]), "n"(set_dx(s2_) * K::PS + set_kc(s2_, j_) * 32))
-#pragma unroll
-    for (int j = 0; j < 4; ++j) QRM_FRAG_READ(f[j], 0, j);
+    constexpr int NF = 4;                   // fragment registers = reads in flight (6 or 8 measure the same)
+    constexpr int NT = 4 * NS;              // fragments, in the order they are used: set by set
+    bf16x8 f[NF];
+    constexpr auto set_row = [](int s2, int j) { return (s2 % NP) + (j & 1) * NP; };
+    constexpr auto set_kc = [](int s2, int j) { return 2 * ((s2 / NP) % KP) + (j >> 1); };
+    constexpr auto set_dx = [](int s2) { return s2 / (NP * KP); };
+    unrolled<NF>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        frag_read<set_dx(t / 4) * K::PS + set_kc(t / 4, t % 4) * 32>(f[t], rowp[set_row(t / 4, t % 4)]);
+    });
     __builtin_amdgcn_sched_barrier(0);
+    unrolled<NT>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        constexpr int s2 = t / 4, j = t % 4;
+        constexpr int dx = set_dx(s2);
+        constexpr int r = set_row(s2, j), kc = set_kc(s2, j);
+        bf16x8 &fr = f[t % NF];
+        // LDS reads return in order: fragment t has landed once at most the NF - 1 reads issued after it
+        // (fewer near the end) are outstanding
+        frag_wait<(t + NF <= NT ? NF - 1 : NT - 1 - t)>(fr);
 #pragma unroll
-    for (int s2 = 0; s2 < NS; ++s2) {
-        const int dx = set_dx(s2);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int r = set_row(s2, j), kc = set_kc(s2, j);
-            // LDS reads return in order: fragment j has landed once at most the three reads issued
-            // after it (none after the last set's) are outstanding
-            if (s2 + 1 < NS) asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(f[j]));
-            else asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(f[j]) : "n"(3 - j));
-#pragma unroll
-            for (int dy = 0; dy < 3; ++dy) {
-                const int orow = r - dy;
-                if (orow >= 0 && orow < RW) {
-                    if (POOL) {
-                        if (!RAGGED || orow < rows_valid) acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow & 1]);
-                    } else if (INIT && !started[orow]) {
-                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[j], zero);
-                        started[orow] = true;
-                    } else {
-                        acc[orow] = mfma32(Wr[dy * 3 + dx][kc], f[j], acc[orow]);
-                    }
+        for (int dy = 0; dy < 3; ++dy) {
+            const int orow = r - dy;
+            if (orow >= 0 && orow < RW) {
+                if (POOL) {
+                    if (!RAGGED || orow < rows_valid) acc[orow & 1] = mfma32(Wr[dy * 3 + dx][kc], fr, acc[orow & 1]);
+                } else if (INIT && !started[orow]) {
+                    acc[orow] = mfma32(Wr[dy * 3 + dx][kc], fr, zero);
+                    started[orow] = true;
+                } else {
+                    acc[orow] = mfma32(Wr[dy * 3 + dx][kc], fr, acc[orow]);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
-            if (s2 + 1 < NS) QRM_FRAG_READ(f[j], s2 + 1, j); // register j is free again: refill it for the next set
-            __builtin_amdgcn_sched_barrier(0);
         }
-    }
-#undef QRM_FRAG_READ
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (t + NF < NT) { // the register is free again: refill it
+            constexpr int u = t + NF;
+            frag_read<set_dx(u / 4) * K::PS + set_kc(u / 4, u % 4) * 32>(fr, rowp[set_row(u / 4, u % 4)]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
 }
 
 template <int C>
