@@ -444,6 +444,20 @@ def bench_stream(env, passes: int, warm_passes: int) -> dict:
             "note": "the uploads follow each other with no gap and the kernels of a chunk take about half as long as its upload: "
                     "the pipeline is bound by the host link, and there is no idle time for a stream tuner to fill",
         }
+    # what the paper's stream planner (Section 5, Algorithm 1) makes of these measurements: the three roles as
+    # stages, one chunk as the baseline batch, the staging buffers and the workspace as the memory per image
+    plan = None
+    if timeline is not None:
+        t_stage = [float(up.mean()) * 1e-3, float(run.mean()) * 1e-3, max(float((tl[:, 4] - tl[:, 3]).mean()) * 1e-3, 1e-6)]
+        u_stage = [3.0 * cfg.H * cfg.W, ctx.qrm_workspace_bytes(chunk, cfg.tile, cfg.tile) / chunk, float(cfg.k + cfg.n + 1)]
+        st, s_plan, m_plan, j_plan, acc = q.qrm_plan_streams(t_stage, u_stage, n_total, chunk, q.QRM_MAX_STREAMS, 64.0 * 2 ** 30,
+                                                             0.01 * max(t_stage), 2)
+        plan = {"stages": ["upload", "kernels", "download"], "t_s_per_chunk": [round(v, 6) for v in t_stage],
+                "bytes_per_image": [round(v, 1) for v in u_stage], "status": st, "streams": s_plan, "micro_batch": m_plan,
+                "predicted_bottleneck_s": round(j_plan, 6),
+                "note": "the planner's cost model divides a stage's time by its streams; the upload stage is one host link, "
+                        "which two concurrent copies share (an earlier version with two uploads in flight reached 0.73 "
+                        "of the link against 0.93-0.95 with one): qrm_detect_host keeps one stream per role"}
     # the link on its own: the same chunks uploaded back to back, nothing else running
     d_stage = torch.empty((chunk, 3, cfg.H, cfg.W), dtype=torch.uint8, device="cuda")
     d_stage.copy_(bufs[0], non_blocking=True)
@@ -481,7 +495,7 @@ def bench_stream(env, passes: int, warm_passes: int) -> dict:
         "extractor_mfma_tflops": round(mfma_flops_per_image * value / 1e12, 2),
         "extractor_frac_of_bf16_peak": round(mfma_flops_per_image * value / 1e12 / PEAK_BF16_TFLOPS, 4),
         "stages": {"bare_upload_GBs": round(link_gbs, 2), "bare_upload_images_per_s": round(link_gbs * 1e9 / (3 * cfg.H * cfg.W), 1),
-                   "resident_images_per_s": round(resident, 1), "timeline": timeline},
+                   "resident_images_per_s": round(resident, 1), "timeline": timeline, "stream_plan": plan},
     }
     log(f"C5: {value:.0f} images/s = {res['roofline']['frac']:.3f} of the bare upload rate ({link_gbs:.1f} GB/s)")
     ctx.close()

@@ -281,6 +281,28 @@ QRM_API qrm_status qrm_detect_verify(qrm_ctx *ctx, const uint8_t *d_images, int6
                                      int32_t *d_matches, uint8_t *d_detected, void *stream);
 
 /*
+ * Adaptive stream / micro-batch planner (Section 5, "Adaptive multi-channel horizontal fusion", Algorithm 1;
+ * cost model at the end of Section 5: a stage whose warm-up time for a baseline batch b0 on one stream was t
+ * takes t / s * m / b0 for a micro-batch m on s streams).  Host-only, no context, touches no device.
+ * h_t HOST f64 [n_stages]: warm-up seconds per stage (> 0); h_u HOST f64 [n_stages]: bytes one sample holds
+ * in that stage (>= 0); B: global batch; b0: the batch the warm-up ran on; P: stream budget over all stages
+ * (>= n_stages); M_cap: memory cap in bytes for sum s[k] * m[k] * u[k]; eps: the smallest drop of the
+ * bottleneck latency (seconds) worth another stream; tau: the search ends after tau scans without such a drop.
+ * Outputs (HOST, caller's): h_s i32 [n_stages] streams per stage; h_m i64 [n_stages] micro-batch per stage;
+ * h_J (may be NULL) predicted bottleneck latency max_k t[k] / s[k] * m[k] / b0 of the plan; h_accepted (may be
+ * NULL) number of streams handed out beyond one per stage.  Steps: one stream per stage and the largest
+ * uniform micro-batch <= B that fits; greedy search (the stage whose extra stream lowers the bottleneck most,
+ * first stage on ties, inside both budgets); leveling (stages at most half as slow as the bottleneck get
+ * min(B / sum s, 2 m) samples if that is more than they have and still fits).
+ * Errors: QRM_E_INVALID (NULL pointer, n_stages outside 1..QRM_PLAN_MAX_STAGES, non-positive time, negative
+ * or NaN size, P < n_stages, B, b0 or tau < 1), QRM_E_UNSUPPORTED (not even one sample per stage fits M_cap).
+ */
+#define QRM_PLAN_MAX_STAGES 64
+QRM_API qrm_status qrm_plan_streams(int32_t n_stages, const double *h_t, const double *h_u, int64_t B, int64_t b0,
+                                    int32_t P, double M_cap, double eps, int32_t tau, int32_t *h_s, int64_t *h_m,
+                                    double *h_J, int32_t *h_accepted);
+
+/*
  * The same path for a batch that lives in HOST memory, streamed through the GPU in chunks (the
  * pipelined detection of Section 5: the transfer of one mini-batch overlaps the kernels of another;
  * Section 7 streams up to a million images this way).  The context owns three (default-priority)

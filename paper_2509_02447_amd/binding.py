@@ -39,10 +39,11 @@ class _RsDesc(C.Structure):
 
 EXPORTS = ["qrm_create", "qrm_destroy", "qrm_last_error", "qrm_set_micro_batch", "qrm_workspace_bytes",
            "qrm_extract_tiles", "qrm_preprocess", "qrm_select_tiles_variance", "qrm_extractor_forward", "qrm_extractor_blocks", "qrm_rs_decode", "qrm_detect",
-           "qrm_detect_host", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
+           "qrm_detect_host", "qrm_plan_streams", "qrm_key_threshold", "qrm_set_key", "qrm_verify_key", "qrm_detect_verify",
            "qrm_profile_enable", "qrm_profile_read", "qrm_profile_read_chunks", "qrm_release_stream", "qrm_detect_static", "qrm_version"]
 DIAG_EXPORTS = ["qrm_diag_set_flags", "qrm_diag_matrix_rate"]      # include/qrm_diag.h: bench and test tooling
 
+QRM_MAX_STREAMS = 8   # include/qrm.h
 QRM_DIAG_NO_FUSED_PAIRS, QRM_DIAG_POISON_WORKSPACE, QRM_DIAG_FUSE_ALWAYS = 1, 2, 4
 (QRM_PROFILE_PAIR_FIRST, QRM_PROFILE_PAIR_MID, QRM_PROFILE_PAIR_LAST, QRM_PROFILE_BLOCK_FIRST, QRM_PROFILE_BLOCK_MID,
  QRM_PROFILE_BLOCK_LAST, QRM_PROFILE_HEAD, QRM_PROFILE_RS_DECODE, QRM_PROFILE_KINDS) = range(9)
@@ -93,6 +94,10 @@ def load_library():
     lib.qrm_detect_host.restype = C.c_int
     lib.qrm_key_threshold.argtypes = [i32, C.c_double]
     lib.qrm_key_threshold.restype = C.c_int32
+    lib.qrm_plan_streams.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(C.c_double), i64, i64, i32, C.c_double,
+                                     C.c_double, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(C.c_double),
+                                     C.POINTER(i32)]
+    lib.qrm_plan_streams.restype = C.c_int
     lib.qrm_set_key.argtypes = [vp, vp, i32]
     lib.qrm_set_key.restype = C.c_int
     lib.qrm_verify_key.argtypes = [vp, vp, i64, vp, vp, vp]
@@ -123,6 +128,17 @@ def version() -> str:
 
 def qrm_key_threshold(n_bits: int, fpr: float) -> int:
     return int(load_library().qrm_key_threshold(int(n_bits), float(fpr)))
+
+
+def qrm_plan_streams(t, u, B: int, b0: int, P: int, M_cap: float, eps: float, tau: int):
+    """-> (status, s list, m list, J, accepted): streams and micro-batch per stage (host-only)."""
+    K = len(t)
+    ta, ua = (C.c_double * K)(*[float(x) for x in t]), (C.c_double * K)(*[float(x) for x in u])
+    s, m = (C.c_int32 * K)(), (C.c_int64 * K)()
+    J, acc = C.c_double(0.0), C.c_int32(0)
+    st = load_library().qrm_plan_streams(K, ta, ua, int(B), int(b0), int(P), float(M_cap), float(eps), int(tau), s, m,
+                                         C.byref(J), C.byref(acc))
+    return int(st), list(s), list(m), float(J.value), int(acc.value)
 
 
 def _fptr(a: Optional[np.ndarray]):

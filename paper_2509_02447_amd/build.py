@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqrm.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["qrm_api.hip", "extractor.hip", "rs_decode.hip", "tiles.hip", "qrm_noalloc.hip", "qrm_diag.hip"]
+SOURCES = ["qrm_api.hip", "extractor.hip", "rs_decode.hip", "tiles.hip", "qrm_noalloc.hip", "qrm_diag.hip", "qrm_plan.hip"]
 HEADERS = ["qrm_internal.h", os.path.join("..", "..", "include", "qrm.h"),
            os.path.join("..", "..", "include", "qrm_diag.h")]
 
