@@ -34,8 +34,24 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
 # kernel, the micro-batch and the image count it was taken on are unchanged; otherwise the line reports null.
 RECORDED_TRAFFIC = {
     # (configuration, launch kind): bytes per launch, where it was measured
-    ("C2", "pair_mid"): {"bytes": 1076853382, "commit": "dae85d0", "images_per_launch": 1024,
-                         "source": "profiles/conv_pair_c2_hbm_traffic.txt"},
+    ("C2", "pair_mid"): {"bytes": 1076929521, "commit": "f08133f", "images_per_launch": 1024,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C2", "pair_last"): {"bytes": 544245792, "commit": "f08133f", "images_per_launch": 1024,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C2", "pair_first"): {"bytes": 571728051, "commit": "f08133f", "images_per_launch": 1024,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C3", "pair_mid"): {"bytes": 4456336948, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C3", "pair_last"): {"bytes": 2318194705, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C3", "pair_first"): {"bytes": 2408639194, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C4", "pair_mid"): {"bytes": 1104996974, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C4", "pair_last"): {"bytes": 573363200, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
+    ("C4", "pair_first"): {"bytes": 596632402, "commit": "f08133f", "images_per_launch": 256,
+                         "source": "profiles/conv_pair_c2_c3_c4_hbm_traffic.txt"},
 }
 
 HOST_THREADS = min(16, os.cpu_count() or 1)
@@ -450,10 +466,12 @@ def bench_stream(env, passes: int, warm_passes: int) -> dict:
     if timeline is not None:
         t_stage = [float(up.mean()) * 1e-3, float(run.mean()) * 1e-3, max(float((tl[:, 4] - tl[:, 3]).mean()) * 1e-3, 1e-6)]
         u_stage = [3.0 * cfg.H * cfg.W, ctx.qrm_workspace_bytes(chunk, cfg.tile, cfg.tile) / chunk, float(cfg.k + cfg.n + 1)]
-        st, s_plan, m_plan, j_plan, acc = q.qrm_plan_streams(t_stage, u_stage, n_total, chunk, q.QRM_MAX_STREAMS, 64.0 * 2 ** 30,
+        in_flight, cap = lanes * chunk, 16.0 * 2 ** 30   # the batch the pipeline holds at a time; memory it may plan with
+        st, s_plan, m_plan, j_plan, acc = q.qrm_plan_streams(t_stage, u_stage, in_flight, chunk, q.QRM_MAX_STREAMS, cap,
                                                              0.01 * max(t_stage), 2)
         plan = {"stages": ["upload", "kernels", "download"], "t_s_per_chunk": [round(v, 6) for v in t_stage],
-                "bytes_per_image": [round(v, 1) for v in u_stage], "status": st, "streams": s_plan, "micro_batch": m_plan,
+                "bytes_per_image": [round(v, 1) for v in u_stage], "global_batch": in_flight, "memory_cap_bytes": cap,
+                "stream_budget": q.QRM_MAX_STREAMS, "status": st, "streams": s_plan, "micro_batch": m_plan,
                 "predicted_bottleneck_s": round(j_plan, 6),
                 "note": "the planner's cost model divides a stage's time by its streams; the upload stage is one host link, "
                         "which two concurrent copies share (an earlier version with two uploads in flight reached 0.73 "
