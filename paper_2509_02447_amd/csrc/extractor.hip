@@ -740,12 +740,15 @@ __global__ __launch_bounds__(64 * kMidWaves, 1) void conv_mid_kernel(const uint8
 //
 // Rows are processed two at a time (the two rings of 8 rows of 66 pixels x 144 bytes fill the LDS).  Step s
 // of an image of h rows, S = ceil(h/2):
-//   A   : s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2 -> +bias (+correction), ReLU,
-//         bf16 -> intermediate ring (zeros outside the tile);  s == S: rows 2S, 2S+1 = zero padding
+//   A   : s < S: intermediate rows 2s, 2s+1 from input rows 2s-1 .. 2s+2; behind its matrix instructions it
+//         waits for the loads it issued a step ago and issues the direct-to-LDS loads of input rows 2s+5, 2s+6
+//         (needed in step s+2); then +bias (+correction), ReLU, bf16 -> intermediate ring (zeros outside the
+//         tile);  s == S: rows 2S, 2S+1 = zero padding
 //   B   : first the epilogue of the rows it accumulated in step s-1 (stores behind which its matrix
 //         instructions then run), then output rows 2j, 2j+1, j = s-2, from intermediate rows 2j-1 .. 2j+2
-//   end : s_waitcnt vmcnt(0) (the loads issued a step ago), then the direct-to-LDS loads of input rows
-//         2s+5 (group A) and 2s+6 (group B), needed in step s+2; one workgroup barrier
+//   end : one workgroup barrier
+// (All loads are group A's: the vector-memory instructions of a compute unit issue in order, and loads issued
+// by group B at the end of a step would sit in front of its own stores at the start of the next.)
 // Row y of either map lives in ring slot (y + 2) mod 8.
 // A workgroup's images follow each other without a gap: see the main loop (virtual rows).
 // The second block's weights are rounded so that the rounding residuals of the nine taps of every
