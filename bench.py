@@ -241,7 +241,11 @@ def bench_resident(env, name: str, steps: int, warmup: int, cpu_sample: int, sta
         "block_last": "conv_mid_kernel, last block (channel sums only)",
     }
     rec = RECORDED_TRAFFIC.get((name, dom))
-    use_rec = bool(rec) and not args.micro_batch and not args.images
+    # a record applies to launches of the size it was taken on (the FLOPs of a launch say how many images it held)
+    flops_per_image_and_launch = {"pair_first": 2 * 9 * (3 + cfg.channels) * cfg.channels, "pair_mid": 2 * 2 * 9 * cfg.channels ** 2,
+                                  "pair_last": 2 * 2 * 9 * cfg.channels ** 2}.get(dom, 0) * cfg.tile * cfg.tile
+    images_per_launch = round(kinds[dom]["flops_per_launch"] / flops_per_image_and_launch) if flops_per_image_and_launch else 0
+    use_rec = bool(rec) and rec["images_per_launch"] == images_per_launch
     roofline = {"kernel": kernel_names.get(dom, dom), "bound": "mfma",
                 "achieved": conv[dom]["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": conv[dom]["frac_of_bf16_peak"],
@@ -250,7 +254,7 @@ def bench_resident(env, name: str, steps: int, warmup: int, cpu_sample: int, sta
                                  f"{rec['commit']} ({rec['source']})") if use_rec else
                                 "no counter run is recorded for this kernel and launch size",
                 "launches_per_step": kinds[dom]["launches_per_step"], "avg_launch_us": kinds[dom]["avg_launch_us"],
-                "flops_per_launch": kinds[dom]["flops_per_launch"],
+                "flops_per_launch": kinds[dom]["flops_per_launch"], "images_per_launch": images_per_launch,
                 "share_of_step_time": round(kinds[dom]["ms_per_step"] / ms_per_step, 4),
                 "timing": f"HIP events around every launch, a second pass of {prof_steps} steps"}
 
